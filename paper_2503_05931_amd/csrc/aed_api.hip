@@ -1,0 +1,770 @@
+// C ABI of the AED decoder library: argument checking, workspace carving, the
+// decode state machine, launch-graph capture/replay and measurement helpers.
+// All device work is in gemm_decode.hip, attn_decode.hip, step_kernels.hip.
+#include <limits.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/aed.h"
+#include "kernels.h"
+
+using namespace aed;
+
+namespace {
+
+constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
+constexpr int kTargetItems = 768;   // work items aimed at per attention launch (3 per CU)
+
+thread_local std::string g_create_error;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Offsets (bytes) of everything carved from the caller's workspace.
+struct Layout {
+    size_t x, q, logits, attn_out, ffn_h;
+    size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished;
+    size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part, counters;
+    size_t k_pool, v_pool, kc, vc;
+    size_t total;
+    int max_pages, n_pages, max_items;
+    size_t pool_layer_elems, cross_layer_elems;
+};
+
+aed_status check_config(const aed_config* c, std::string& err) {
+    auto bad = [&](const char* m) { err = m; return AED_EINVAL; };
+    auto unsup = [&](const char* m) { err = m; return AED_EUNSUPPORTED; };
+    if (!c) return bad("config is NULL");
+    if (c->struct_size != sizeof(aed_config)) return bad("aed_config.struct_size does not match this library");
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->head_dim < 1 || c->d_ffn < 1 || c->vocab < 1 ||
+        c->max_positions < 1)
+        return bad("model dimensions must be positive");
+    if ((long long)c->n_heads * c->head_dim != c->d_model) return bad("n_heads * head_dim != d_model");
+    if (c->dtype != 0 && c->dtype != 1) return bad("dtype must be 0 (float32) or 1 (bfloat16)");
+    if (c->max_batch < 1 || c->max_total_enc_frames < 1 || c->max_dec_len < 1) return bad("capacities must be positive");
+    if (c->max_total_enc_frames < c->max_batch) return bad("max_total_enc_frames < max_batch (every sequence has >= 1 frame)");
+    if (c->kv_pages < 0) return bad("kv_pages < 0");
+    if (!(c->ln_eps > 0.f)) return bad("ln_eps must be > 0");
+    if (c->eos_id >= c->vocab || c->pad_id < 0) return bad("eos_id / pad_id out of range");
+    if (c->norm_type != 0) return unsup("only LayerNorm (norm_type 0) is built");
+    if (c->page_size != kPage) return unsup("page_size must be 16");
+    if (c->head_dim != 64 && c->head_dim != 128) return unsup("head_dim must be 64 or 128");
+    if (c->d_model % 256 != 0 || c->d_model > 1024) return unsup("d_model must be a multiple of 256, at most 1024");
+    if (c->d_ffn % 256 != 0) return unsup("d_ffn must be a multiple of 256");
+    if (c->vocab % 64 != 0) return unsup("vocab must be a multiple of 64");
+    if (c->max_batch > 65535) return unsup("max_batch above 65535");
+    return AED_OK;
+}
+
+void make_layout(const aed_config* c, Layout* L) {
+    const size_t e = c->dtype == 1 ? 2 : 4;
+    const size_t B = c->max_batch, d = c->d_model, H = c->n_heads, Dh = c->head_dim;
+    L->max_pages = (c->max_dec_len + kPage - 1) / kPage;
+    L->n_pages = c->kv_pages > 0 ? c->kv_pages : (int)(B * L->max_pages);
+    L->max_items = c->max_total_enc_frames / 64 + c->max_batch;
+    L->pool_layer_elems = (size_t)L->n_pages * H * kPage * Dh;
+    L->cross_layer_elems = (size_t)c->max_total_enc_frames * d;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L->x = take(B * d * 4);
+    L->q = take(B * d * 4);
+    L->logits = take(B * (size_t)c->vocab * 4);
+    L->attn_out = take(B * d * e);
+    L->ffn_h = take(B * (size_t)c->d_ffn * e);
+    L->seq_len = take(B * 4);
+    L->n_gen = take(B * 4);
+    L->finished = take(B * 4);
+    L->cur_tok = take(B * 4);
+    L->limit = take(B * 4);
+    L->limits_in = take(B * 4);
+    L->n_finished = take(256);
+    L->prompt_buf = take(B * (size_t)c->max_dec_len * 4);
+    L->out_buf = take(B * (size_t)c->max_dec_len * 4);
+    L->page_table = take(B * (size_t)L->max_pages * 4);
+    L->enc_off = take((B + 1) * 4);
+    L->row_map = take((size_t)c->max_total_enc_frames * 4);
+    L->items = take((size_t)L->max_items * 16);
+    L->part = take(B * H * kMaxChunks * (Dh + 2) * 4);
+    L->counters = take(B * H * 4);
+    L->k_pool = take(L->pool_layer_elems * c->n_layers * e);
+    L->v_pool = take(L->pool_layer_elems * c->n_layers * e);
+    L->kc = take(L->cross_layer_elems * c->n_layers * e);
+    L->vc = take(L->cross_layer_elems * c->n_layers * e);
+    L->total = off;
+}
+
+struct GraphKey {
+    int batch = -1, n_items = 0, self_chunk = 0, self_nchunks = 0, prompt_len = 0, max_new = 0;
+    bool operator==(const GraphKey& o) const {
+        return batch == o.batch && n_items == o.n_items && self_chunk == o.self_chunk &&
+               self_nchunks == o.self_nchunks && prompt_len == o.prompt_len && max_new == o.max_new;
+    }
+};
+
+}  // namespace
+
+struct aed_decoder {
+    aed_config cfg;
+    Dtype dt;
+    size_t esz;
+    Layout lay;
+    std::vector<aed_layer_weights> layers;
+    aed_weights w;
+    hipStream_t stream;
+    char* ws;
+    // host-side state
+    enum State { NO_BATCH, STEPPING, CONSUMED } state = NO_BATCH;
+    int batch = 0;
+    int host_pos = 0;     // positions fed so far (step API)
+    int pages_used = 0;
+    int n_items = 0;
+    int self_chunk = 64, self_nchunks = 1;
+    int last_prompt_len = 0, last_max_new = 0;
+    long long total_enc = 0;
+    const void* last_enc = nullptr;
+    bool last_enc_padded = false;
+    std::vector<int> enc_lens, enc_off, page_table;
+    int* pin_poll = nullptr;  // pinned host memory for the finished-count poll
+    hipEvent_t poll_event[2] = {nullptr, nullptr};
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    hipGraphExec_t gexec = nullptr;
+    GraphKey gkey;
+    std::string err;
+
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+    StateArgs state_args(int prompt_len, int max_new) const {
+        StateArgs st;
+        st.seq_len = at<int>(lay.seq_len);
+        st.n_gen = at<int>(lay.n_gen);
+        st.finished = at<int>(lay.finished);
+        st.cur_tok = at<int>(lay.cur_tok);
+        st.limit = at<int>(lay.limit);
+        st.n_finished = at<int>(lay.n_finished);
+        st.prompt = prompt_len > 0 ? at<int>(lay.prompt_buf) : nullptr;
+        st.out_tokens = at<int>(lay.out_buf);
+        st.prompt_len = prompt_len;
+        st.prompt_stride = prompt_len;
+        st.out_stride = cfg.max_dec_len;
+        st.max_new = max_new;
+        st.eos_id = cfg.eos_id;
+        st.pad_id = cfg.pad_id;
+        st.batch = batch;
+        st.vocab = cfg.vocab;
+        return st;
+    }
+};
+
+namespace {
+
+aed_status fail(aed_decoder* d, aed_status st, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (d) d->err = buf; else g_create_error = buf;
+    return st;
+}
+
+#define HIP_TRY(d, expr)                                                                          \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess) return fail(d, AED_EHIP, "%s: %s", #expr, hipGetErrorString(e_));  \
+    } while (0)
+
+// Keys per attention work item: enough items to occupy the GPU, at least 64
+// keys each, at most kMaxChunks items per (sequence, head).
+int pick_chunk(long long total_keys, int max_len, int n_heads) {
+    long long c = (total_keys * n_heads + kTargetItems - 1) / kTargetItems;
+    long long lo = ((long long)max_len + kMaxChunks - 1) / kMaxChunks;
+    c = std::max(c, lo);
+    c = std::max<long long>(64, (c + 63) / 64 * 64);
+    return (int)std::min<long long>(c, 1 << 20);
+}
+
+// ---------------------------------------------------------------- kernel argument builders
+GemmArgs gemm_base(const aed_decoder* d) {
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.ln_eps = d->cfg.ln_eps;
+    g.M = d->batch;
+    g.n_heads = d->cfg.n_heads;
+    g.head_dim = d->cfg.head_dim;
+    g.d_model = d->cfg.d_model;
+    return g;
+}
+
+hipError_t k_ln_qkv(aed_decoder* d, int l) {
+    const aed_layer_weights& w = d->layers[l];
+    GemmArgs g = gemm_base(d);
+    g.A = d->at<float>(d->lay.x);
+    g.W = w.w_qkv; g.bias = w.b_qkv; g.ln_g = w.ln1_g; g.ln_b = w.ln1_b;
+    g.N = 3 * d->cfg.d_model; g.K = d->cfg.d_model;
+    g.out = d->at<float>(d->lay.q);
+    g.k_pool = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
+    g.v_pool = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
+    g.page_table = d->at<int>(d->lay.page_table);
+    g.max_pages = d->lay.max_pages;
+    g.seq_len = d->at<int>(d->lay.seq_len);
+    g.finished = d->at<int>(d->lay.finished);
+    return launch_gemm(d->dt, PRO_LN, EPI_QKV, g, d->stream);
+}
+
+AttnArgs attn_base(const aed_decoder* d) {
+    AttnArgs a;
+    memset(&a, 0, sizeof a);
+    a.q = d->at<float>(d->lay.q);
+    a.out = d->ws + d->lay.attn_out;
+    a.finished = d->at<int>(d->lay.finished);
+    a.part = d->at<float>(d->lay.part);
+    a.counters = d->at<int>(d->lay.counters);
+    a.max_chunks = kMaxChunks;
+    a.n_heads = d->cfg.n_heads;
+    a.head_dim = d->cfg.head_dim;
+    a.batch = d->batch;
+    a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)d->cfg.head_dim));
+    return a;
+}
+
+hipError_t k_self_attn(aed_decoder* d, int l) {
+    AttnArgs a = attn_base(d);
+    a.K = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
+    a.V = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
+    a.page_table = d->at<int>(d->lay.page_table);
+    a.max_pages = d->lay.max_pages;
+    a.seq_len = d->at<int>(d->lay.seq_len);
+    a.chunk = d->self_chunk;
+    a.n_chunks_max = d->self_nchunks;
+    return launch_attn_self(d->dt, a, d->stream);
+}
+
+hipError_t k_resid(aed_decoder* d, const void* A, const void* W, const void* bias, int K) {
+    GemmArgs g = gemm_base(d);
+    g.A = A; g.W = W; g.bias = bias;
+    g.N = d->cfg.d_model; g.K = K;
+    g.out = d->at<float>(d->lay.x);
+    return launch_gemm(d->dt, PRO_T, EPI_RESID, g, d->stream);
+}
+
+hipError_t k_ln_crossq(aed_decoder* d, int l) {
+    const aed_layer_weights& w = d->layers[l];
+    GemmArgs g = gemm_base(d);
+    g.A = d->at<float>(d->lay.x);
+    g.W = w.w_cq; g.bias = w.b_cq; g.ln_g = w.ln2_g; g.ln_b = w.ln2_b;
+    g.N = d->cfg.d_model; g.K = d->cfg.d_model;
+    g.out = d->at<float>(d->lay.q);
+    return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
+}
+
+hipError_t k_cross_attn(aed_decoder* d, int l) {
+    AttnArgs a = attn_base(d);
+    a.K = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
+    a.V = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
+    a.items = d->at<int4>(d->lay.items);
+    a.n_items = d->n_items;
+    a.enc_off = d->at<int>(d->lay.enc_off);
+    a.t_cap = d->cfg.max_total_enc_frames;
+    return launch_attn_cross(d->dt, a, d->stream);
+}
+
+hipError_t k_ln_ffn1(aed_decoder* d, int l) {
+    const aed_layer_weights& w = d->layers[l];
+    GemmArgs g = gemm_base(d);
+    g.A = d->at<float>(d->lay.x);
+    g.W = w.w_ff1; g.bias = w.b_ff1; g.ln_g = w.ln3_g; g.ln_b = w.ln3_b;
+    g.N = d->cfg.d_ffn; g.K = d->cfg.d_model;
+    g.out = d->ws + d->lay.ffn_h;
+    return launch_gemm(d->dt, PRO_LN, EPI_RELU_T, g, d->stream);
+}
+
+hipError_t k_ln_vocab(aed_decoder* d) {
+    GemmArgs g = gemm_base(d);
+    g.A = d->at<float>(d->lay.x);
+    g.W = d->w.w_out; g.bias = d->w.b_out; g.ln_g = d->w.lnf_g; g.ln_b = d->w.lnf_b;
+    g.N = d->cfg.vocab; g.K = d->cfg.d_model;
+    g.out = d->at<float>(d->lay.logits);
+    return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
+}
+
+hipError_t k_cross_kv(aed_decoder* d, int l) {
+    const aed_layer_weights& w = d->layers[l];
+    GemmArgs g = gemm_base(d);
+    g.A = d->last_enc;
+    g.a_row_map = d->last_enc_padded ? d->at<int>(d->lay.row_map) : nullptr;
+    g.W = w.w_ckv; g.bias = w.b_ckv;
+    g.M = (int)d->total_enc; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
+    g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
+    g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
+    g.t_cap = d->cfg.max_total_enc_frames;
+    return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);
+}
+
+hipError_t k_class(aed_decoder* d, int cls, int l) {
+    const aed_layer_weights& w = d->layers[l];
+    switch (cls) {
+        case AED_K_LN_QKV: return k_ln_qkv(d, l);
+        case AED_K_SELF_ATTN: return k_self_attn(d, l);
+        case AED_K_SELF_OUT: return k_resid(d, d->ws + d->lay.attn_out, w.w_o, w.b_o, d->cfg.d_model);
+        case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
+        case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
+        case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, w.w_co, w.b_co, d->cfg.d_model);
+        case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
+        case AED_K_FFN2: return k_resid(d, d->ws + d->lay.ffn_h, w.w_ff2, w.b_ff2, d->cfg.d_ffn);
+        case AED_K_CROSS_KV: return k_cross_kv(d, l);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// One decoder step for the whole batch, enqueued on the stream.
+hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* step_out) {
+    hipError_t e;
+    e = launch_embed(d->dt, d->at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
+                     d->cfg.max_positions, d->cfg.emb_scale, d->stream);
+    if (e != hipSuccess) return e;
+    for (int l = 0; l < d->cfg.n_layers; ++l)
+        for (int cls = AED_K_LN_QKV; cls <= AED_K_FFN2; ++cls)
+            if ((e = k_class(d, cls, l)) != hipSuccess) return e;
+    if ((e = k_ln_vocab(d)) != hipSuccess) return e;
+    return launch_sample(d->at<float>(d->lay.logits), st, greedy, step_out, d->stream);
+}
+
+aed_status check_weights(const aed_config* c, const aed_weights* w) {
+    if (!w) return fail(nullptr, AED_EINVAL, "weights is NULL");
+    if (!w->tok_emb || !w->pos_emb || !w->lnf_g || !w->lnf_b || !w->w_out || !w->layers)
+        return fail(nullptr, AED_EINVAL, "a required top-level weight pointer is NULL");
+    for (int l = 0; l < c->n_layers; ++l) {
+        const aed_layer_weights& x = w->layers[l];
+        if (!x.ln1_g || !x.ln1_b || !x.w_qkv || !x.w_o || !x.ln2_g || !x.ln2_b || !x.w_cq || !x.w_ckv || !x.w_co ||
+            !x.ln3_g || !x.ln3_b || !x.w_ff1 || !x.w_ff2)
+            return fail(nullptr, AED_EINVAL, "layer %d: a required weight pointer is NULL", l);
+    }
+    return AED_OK;
+}
+
+aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, const int32_t* enc_lens,
+                       int32_t batch) {
+    if (!d) return AED_EINVAL;
+    if (!enc || !enc_lens) return fail(d, AED_EINVAL, "enc_states / enc_lens is NULL");
+    if (batch < 1) return fail(d, AED_EINVAL, "batch must be >= 1");
+    if (batch > d->cfg.max_batch) return fail(d, AED_ECAPACITY, "batch %d > max_batch %d", batch, d->cfg.max_batch);
+    long long total = 0;
+    int max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (enc_lens[b] < 1) return fail(d, AED_EINVAL, "enc_lens[%d] = %d (must be >= 1)", b, enc_lens[b]);
+        if (padded && enc_lens[b] > t_max) return fail(d, AED_EINVAL, "enc_lens[%d] = %d > t_max %d", b, enc_lens[b], t_max);
+        total += enc_lens[b];
+        max_len = std::max(max_len, enc_lens[b]);
+    }
+    if (total > d->cfg.max_total_enc_frames)
+        return fail(d, AED_ECAPACITY, "sum(enc_lens) = %lld > max_total_enc_frames %d", total, d->cfg.max_total_enc_frames);
+
+    // host tables: frame offsets, cross-attention work list, optional row map
+    std::vector<int> off(batch + 1, 0);
+    for (int b = 0; b < batch; ++b) off[b + 1] = off[b] + enc_lens[b];
+    const int chunk = pick_chunk(total, max_len, d->cfg.n_heads);
+    std::vector<int4> items;
+    for (int b = 0; b < batch; ++b) {
+        const int nc = (enc_lens[b] + chunk - 1) / chunk;
+        for (int c = 0; c < nc; ++c) {
+            int4 it;
+            it.x = b; it.y = c * chunk; it.z = std::min(chunk, enc_lens[b] - c * chunk); it.w = c | (nc << 16);
+            items.push_back(it);
+        }
+    }
+    if ((int)items.size() > d->lay.max_items) return fail(d, AED_ECAPACITY, "cross-attention work list overflow");
+
+    HIP_TRY(d, hipStreamSynchronize(d->stream));  // the previous batch's work is done with the old tables
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.enc_off), off.data(), off.size() * 4, hipMemcpyHostToDevice, d->stream));
+    HIP_TRY(d, hipMemcpyAsync(d->at<int4>(d->lay.items), items.data(), items.size() * 16, hipMemcpyHostToDevice, d->stream));
+    if (padded) {
+        std::vector<int> map((size_t)total);
+        for (int b = 0; b < batch; ++b)
+            for (int t = 0; t < enc_lens[b]; ++t) map[(size_t)off[b] + t] = b * t_max + t;
+        HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.row_map), map.data(), map.size() * 4, hipMemcpyHostToDevice, d->stream));
+    }
+    d->batch = batch;
+    d->n_items = (int)items.size();
+    d->total_enc = total;
+    d->last_enc = enc;
+    d->last_enc_padded = padded;
+    d->enc_lens.assign(enc_lens, enc_lens + batch);
+    d->enc_off = off;
+    d->host_pos = 0;
+    d->pages_used = 0;
+    d->page_table.assign((size_t)batch * d->lay.max_pages, 0);
+    d->self_chunk = pick_chunk((long long)batch * d->cfg.max_dec_len, d->cfg.max_dec_len, d->cfg.n_heads);
+    d->self_nchunks = (d->cfg.max_dec_len + d->self_chunk - 1) / d->self_chunk;
+    d->state = aed_decoder::NO_BATCH;
+
+    StateArgs st = d->state_args(0, 0);
+    HIP_TRY(d, launch_reset(st, nullptr, 0, d->stream));
+    for (int l = 0; l < d->cfg.n_layers; ++l) HIP_TRY(d, k_cross_kv(d, l));
+    HIP_TRY(d, hipStreamSynchronize(d->stream));  // host vectors above go out of scope
+    d->state = aed_decoder::STEPPING;
+    return AED_OK;
+}
+
+aed_status upload_page_table(aed_decoder* d) {
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.page_table), d->page_table.data(), d->page_table.size() * 4,
+                              hipMemcpyHostToDevice, d->stream));
+    return AED_OK;
+}
+
+}  // namespace
+
+// ===================================================================== C ABI
+extern "C" {
+
+aed_status aed_workspace_bytes(const aed_config* cfg, size_t* bytes) {
+    std::string err;
+    aed_status st = check_config(cfg, err);
+    if (st != AED_OK) { g_create_error = err; return st; }
+    if (!bytes) return fail(nullptr, AED_EINVAL, "bytes is NULL");
+    Layout L;
+    make_layout(cfg, &L);
+    *bytes = L.total;
+    return AED_OK;
+}
+
+aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights, void* workspace,
+                              size_t workspace_bytes, void* hip_stream, aed_decoder** out) {
+    std::string err;
+    aed_status st = check_config(cfg, err);
+    if (st != AED_OK) { g_create_error = err; return st; }
+    if (!out) return fail(nullptr, AED_EINVAL, "out is NULL");
+    *out = nullptr;
+    if ((st = check_weights(cfg, weights)) != AED_OK) return st;
+    Layout L;
+    make_layout(cfg, &L);
+    if (!workspace) return fail(nullptr, AED_EINVAL, "workspace is NULL");
+    if ((uintptr_t)workspace % 256 != 0) return fail(nullptr, AED_EINVAL, "workspace must be 256-byte aligned");
+    if (workspace_bytes < L.total)
+        return fail(nullptr, AED_EINVAL, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+
+    aed_decoder* d = new aed_decoder();
+    d->cfg = *cfg;
+    d->dt = cfg->dtype == 1 ? kBF16 : kF32;
+    d->esz = cfg->dtype == 1 ? 2 : 4;
+    d->lay = L;
+    d->layers.assign(weights->layers, weights->layers + cfg->n_layers);
+    d->w = *weights;
+    d->w.layers = d->layers.data();
+    d->stream = static_cast<hipStream_t>(hip_stream);
+    d->ws = static_cast<char*>(workspace);
+    auto cleanup = [&](hipError_t e, const char* what) {
+        fail(nullptr, AED_EHIP, "%s: %s", what, hipGetErrorString(e));
+        aed_decoder_destroy(d);
+        return AED_EHIP;
+    };
+    hipError_t e;
+    if ((e = hipHostMalloc(reinterpret_cast<void**>(&d->pin_poll), 256, hipHostMallocDefault)) != hipSuccess)
+        return cleanup(e, "hipHostMalloc");
+    d->pin_poll[0] = d->pin_poll[1] = 0;
+    for (int i = 0; i < 2; ++i)
+        if ((e = hipEventCreateWithFlags(&d->poll_event[i], hipEventDisableTiming)) != hipSuccess)
+            return cleanup(e, "hipEventCreate");
+    if ((e = hipEventCreate(&d->t0)) != hipSuccess) return cleanup(e, "hipEventCreate");
+    if ((e = hipEventCreate(&d->t1)) != hipSuccess) return cleanup(e, "hipEventCreate");
+    // counters of the split-K merge start at zero and return to zero after every launch
+    if ((e = hipMemsetAsync(d->ws + L.counters, 0, (size_t)cfg->max_batch * cfg->n_heads * 4, d->stream)) != hipSuccess)
+        return cleanup(e, "hipMemsetAsync");
+    if ((e = hipStreamSynchronize(d->stream)) != hipSuccess) return cleanup(e, "hipStreamSynchronize");
+    *out = d;
+    return AED_OK;
+}
+
+aed_status aed_decoder_destroy(aed_decoder* d) {
+    if (!d) return AED_OK;
+    (void)hipStreamSynchronize(d->stream);
+    if (d->gexec) (void)hipGraphExecDestroy(d->gexec);
+    for (int i = 0; i < 2; ++i)
+        if (d->poll_event[i]) (void)hipEventDestroy(d->poll_event[i]);
+    if (d->t0) (void)hipEventDestroy(d->t0);
+    if (d->t1) (void)hipEventDestroy(d->t1);
+    if (d->pin_poll) (void)hipHostFree(d->pin_poll);
+    delete d;
+    return AED_OK;
+}
+
+aed_status aed_cross_kv_precompute(aed_decoder* d, const void* enc_states, const int32_t* enc_lens, int32_t batch) {
+    return start_batch(d, enc_states, false, 0, enc_lens, batch);
+}
+
+aed_status aed_cross_kv_precompute_padded(aed_decoder* d, const void* enc_padded, int32_t t_max,
+                                          const int32_t* enc_lens, int32_t batch) {
+    if (d && t_max < 1) return fail(d, AED_EINVAL, "t_max must be >= 1");
+    return start_batch(d, enc_padded, true, t_max, enc_lens, batch);
+}
+
+aed_status aed_decode_step(aed_decoder* d, const int32_t* tokens_in, int32_t* tokens_out, float* logits_out) {
+    if (!d) return AED_EINVAL;
+    if (d->state != aed_decoder::STEPPING)
+        return fail(d, AED_ESTATE, "aed_decode_step needs a batch started by aed_cross_kv_precompute");
+    if (!tokens_in) return fail(d, AED_EINVAL, "tokens_in is NULL");
+    if (d->host_pos >= d->cfg.max_dec_len || d->host_pos >= d->cfg.max_positions)
+        return fail(d, AED_ECAPACITY, "position %d exceeds max_dec_len %d / max_positions %d", d->host_pos,
+                    d->cfg.max_dec_len, d->cfg.max_positions);
+    if (d->host_pos % kPage == 0) {  // every sequence enters a new page
+        if (d->pages_used + d->batch > d->lay.n_pages)
+            return fail(d, AED_ECAPACITY, "self-attention page pool exhausted (%d pages)", d->lay.n_pages);
+        const int blk = d->host_pos / kPage;
+        for (int b = 0; b < d->batch; ++b) d->page_table[(size_t)b * d->lay.max_pages + blk] = d->pages_used++;
+        aed_status st = upload_page_table(d);
+        if (st != AED_OK) return st;
+    }
+    StateArgs st = d->state_args(0, 0);
+    HIP_TRY(d, launch_set_tokens(st.cur_tok, tokens_in, 1, d->batch, d->stream));
+    HIP_TRY(d, enqueue_step(d, st, 0, tokens_out));
+    if (logits_out)
+        HIP_TRY(d, hipMemcpyAsync(logits_out, d->at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4,
+                                  hipMemcpyDeviceToDevice, d->stream));
+    d->host_pos += 1;
+    return AED_OK;
+}
+
+aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prompt_len, int32_t max_new,
+                             const int32_t* max_new_per_seq, int32_t* out_tokens, int32_t* out_lens) {
+    if (!d) return AED_EINVAL;
+    if (d->state == aed_decoder::NO_BATCH)
+        return fail(d, AED_ESTATE, "aed_greedy_decode needs a batch started by aed_cross_kv_precompute");
+    if (!prompt || !out_tokens || !out_lens) return fail(d, AED_EINVAL, "prompt / out_tokens / out_lens is NULL");
+    if (prompt_len < 1 || max_new < 1) return fail(d, AED_EINVAL, "prompt_len and max_new must be >= 1");
+    if (max_new_per_seq) {
+        if (d->cfg.eos_id < 0) return fail(d, AED_EINVAL, "max_new_per_seq needs eos_id >= 0");
+        for (int b = 0; b < d->batch; ++b)
+            if (max_new_per_seq[b] < 1) return fail(d, AED_EINVAL, "max_new_per_seq[%d] < 1", b);
+    }
+    const int total_len = prompt_len + max_new;
+    if (total_len > d->cfg.max_dec_len || total_len > d->cfg.max_positions)
+        return fail(d, AED_ECAPACITY, "prompt_len + max_new = %d exceeds max_dec_len %d / max_positions %d", total_len,
+                    d->cfg.max_dec_len, d->cfg.max_positions);
+    // pages: block-major, only the blocks a sequence can reach
+    const int B = d->batch, MP = d->lay.max_pages;
+    std::vector<int> need(B);
+    int max_need = 0;
+    long long pages = 0;
+    for (int b = 0; b < B; ++b) {
+        const int n = max_new_per_seq ? std::min(max_new, max_new_per_seq[b]) : max_new;
+        need[b] = (prompt_len + n + kPage - 1) / kPage;
+        max_need = std::max(max_need, need[b]);
+        pages += need[b];
+    }
+    if (pages > d->lay.n_pages)
+        return fail(d, AED_ECAPACITY, "self-attention page pool too small: %lld pages needed, %d available", pages,
+                    d->lay.n_pages);
+    std::fill(d->page_table.begin(), d->page_table.end(), 0);
+    int next = 0;
+    for (int blk = 0; blk < max_need; ++blk)
+        for (int b = 0; b < B; ++b)
+            if (blk < need[b]) d->page_table[(size_t)b * MP + blk] = next++;
+    d->pages_used = next;
+    aed_status rc = upload_page_table(d);
+    if (rc != AED_OK) return rc;
+    if (max_new_per_seq)
+        HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.limits_in), max_new_per_seq, (size_t)B * 4, hipMemcpyHostToDevice,
+                                  d->stream));
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.prompt_buf), prompt, (size_t)B * prompt_len * 4,
+                              hipMemcpyDeviceToDevice, d->stream));
+    d->self_chunk = pick_chunk((long long)B * total_len, total_len, d->cfg.n_heads);
+    d->self_nchunks = (total_len + d->self_chunk - 1) / d->self_chunk;
+    d->last_prompt_len = prompt_len;
+    d->last_max_new = max_new;
+    StateArgs st = d->state_args(prompt_len, max_new);
+    HIP_TRY(d, launch_reset(st, max_new_per_seq ? d->at<int>(d->lay.limits_in) : nullptr, 1, d->stream));
+    d->state = aed_decoder::CONSUMED;
+
+    // one launch graph per shape; replayed for every step
+    const bool use_graph = d->stream != nullptr;
+    if (use_graph) {
+        GraphKey key;
+        key.batch = B; key.n_items = d->n_items; key.self_chunk = d->self_chunk; key.self_nchunks = d->self_nchunks;
+        key.prompt_len = prompt_len; key.max_new = max_new;
+        if (!d->gexec || !(key == d->gkey)) {
+            if (d->gexec) { (void)hipGraphExecDestroy(d->gexec); d->gexec = nullptr; }
+            hipGraph_t graph = nullptr;
+            HIP_TRY(d, hipStreamBeginCapture(d->stream, hipStreamCaptureModeThreadLocal));
+            hipError_t e = enqueue_step(d, st, 1, nullptr);
+            hipError_t e2 = hipStreamEndCapture(d->stream, &graph);
+            if (e != hipSuccess || e2 != hipSuccess) {
+                if (graph) (void)hipGraphDestroy(graph);
+                return fail(d, AED_EHIP, "graph capture: %s", hipGetErrorString(e != hipSuccess ? e : e2));
+            }
+            e = hipGraphInstantiate(&d->gexec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) { d->gexec = nullptr; return fail(d, AED_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+            d->gkey = key;
+        }
+    }
+    // Early stop: every poll_every steps the finished count is copied to pinned
+    // memory; completed polls are read without blocking, and the host runs at
+    // most two polls ahead of the device.
+    const int n_steps = prompt_len - 1 + max_new;
+    const bool can_stop_early = d->cfg.eos_id >= 0;
+    const int poll_every = 8;
+    int issued = 0, seen = 0;
+    bool done = false;
+    for (int s = 0; s < n_steps && !done; ++s) {
+        if (use_graph) HIP_TRY(d, hipGraphLaunch(d->gexec, d->stream));
+        else HIP_TRY(d, enqueue_step(d, st, 1, nullptr));
+        if (!can_stop_early) continue;
+        while (seen < issued && hipEventQuery(d->poll_event[seen & 1]) == hipSuccess) {
+            done = done || d->pin_poll[seen & 1] >= B;
+            ++seen;
+        }
+        if (done || (s + 1) % poll_every != 0) continue;
+        if (issued - seen >= 2) {
+            HIP_TRY(d, hipEventSynchronize(d->poll_event[seen & 1]));
+            done = d->pin_poll[seen & 1] >= B;
+            ++seen;
+            if (done) break;
+        }
+        HIP_TRY(d, hipMemcpyAsync(&d->pin_poll[issued & 1], st.n_finished, 4, hipMemcpyDeviceToHost, d->stream));
+        HIP_TRY(d, hipEventRecord(d->poll_event[issued & 1], d->stream));
+        ++issued;
+    }
+    (void)hipGetLastError();  // hipEventQuery's "not ready" is not an error
+    HIP_TRY(d, launch_copy_out(st, out_tokens, out_lens, d->stream));
+    HIP_TRY(d, hipStreamSynchronize(d->stream));
+    return AED_OK;
+}
+
+const char* aed_last_error(const aed_decoder* d) { return d ? d->err.c_str() : g_create_error.c_str(); }
+
+int64_t aed_layer_matrix_params(const aed_config* c) {
+    if (!c) return 0;
+    const int64_t d = c->d_model, F = c->d_ffn;
+    return ((3 * d * d + d * d) + (d * d + 2 * d * d + d * d) + 2 * d * F) * c->n_layers;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------- inspection / measurement
+namespace {
+void to_f32_host(const void* src, size_t n, bool bf16, float* dst) {
+    if (!bf16) { memcpy(dst, src, n * 4); return; }
+    const uint16_t* p = static_cast<const uint16_t*>(src);
+    for (size_t i = 0; i < n; ++i) {
+        uint32_t u = (uint32_t)p[i] << 16;
+        memcpy(dst + i, &u, 4);
+    }
+}
+}  // namespace
+
+extern "C" {
+
+aed_status aed_read_cross_kv(aed_decoder* d, int32_t layer, int32_t seq, float* k_out, float* v_out) {
+    if (!d) return AED_EINVAL;
+    if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
+    if (layer < 0 || layer >= d->cfg.n_layers || seq < 0 || seq >= d->batch || !k_out || !v_out)
+        return fail(d, AED_EINVAL, "bad layer / seq / buffer");
+    HIP_TRY(d, hipStreamSynchronize(d->stream));
+    const int T = d->enc_lens[seq], Dh = d->cfg.head_dim, H = d->cfg.n_heads, dm = d->cfg.d_model;
+    std::vector<char> tmp((size_t)T * Dh * d->esz);
+    std::vector<float> f((size_t)T * Dh);
+    for (int which = 0; which < 2; ++which) {
+        const char* base = d->ws + (which ? d->lay.vc : d->lay.kc) + (size_t)layer * d->lay.cross_layer_elems * d->esz;
+        float* out = which ? v_out : k_out;
+        for (int h = 0; h < H; ++h) {
+            const char* src = base + ((size_t)h * d->cfg.max_total_enc_frames + d->enc_off[seq]) * Dh * d->esz;
+            HIP_TRY(d, hipMemcpy(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost));
+            to_f32_host(tmp.data(), f.size(), d->dt == kBF16, f.data());
+            for (int t = 0; t < T; ++t) memcpy(out + (size_t)t * dm + h * Dh, f.data() + (size_t)t * Dh, Dh * 4);
+        }
+    }
+    return AED_OK;
+}
+
+aed_status aed_read_self_kv(aed_decoder* d, int32_t layer, int32_t seq, float* k_out, float* v_out,
+                            int32_t* n_positions) {
+    if (!d) return AED_EINVAL;
+    if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
+    if (layer < 0 || layer >= d->cfg.n_layers || seq < 0 || seq >= d->batch || !k_out || !v_out || !n_positions)
+        return fail(d, AED_EINVAL, "bad layer / seq / buffer");
+    HIP_TRY(d, hipStreamSynchronize(d->stream));
+    int n = 0;
+    HIP_TRY(d, hipMemcpy(&n, d->at<int>(d->lay.seq_len) + seq, 4, hipMemcpyDeviceToHost));
+    n = std::min(n, d->cfg.max_dec_len);
+    *n_positions = n;
+    const int Dh = d->cfg.head_dim, H = d->cfg.n_heads, dm = d->cfg.d_model;
+    std::vector<char> tmp((size_t)kPage * Dh * d->esz);
+    std::vector<float> f((size_t)kPage * Dh);
+    for (int which = 0; which < 2; ++which) {
+        const char* base = d->ws + (which ? d->lay.v_pool : d->lay.k_pool) + (size_t)layer * d->lay.pool_layer_elems * d->esz;
+        float* out = which ? v_out : k_out;
+        for (int blk = 0; blk * kPage < n; ++blk) {
+            const int page = d->page_table[(size_t)seq * d->lay.max_pages + blk];
+            for (int h = 0; h < H; ++h) {
+                const char* src = base + ((size_t)page * H + h) * kPage * Dh * d->esz;
+                HIP_TRY(d, hipMemcpy(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost));
+                to_f32_host(tmp.data(), f.size(), d->dt == kBF16, f.data());
+                for (int s = 0; s < kPage && blk * kPage + s < n; ++s)
+                    memcpy(out + (size_t)(blk * kPage + s) * dm + h * Dh, f.data() + (size_t)s * Dh, Dh * 4);
+            }
+        }
+    }
+    return AED_OK;
+}
+
+aed_status aed_time_kernels(aed_decoder* d, int32_t cls, int32_t reps, float* ms_total, int32_t* launches) {
+    if (!d) return AED_EINVAL;
+    if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
+    if (!ms_total || !launches || reps < 1) return fail(d, AED_EINVAL, "bad arguments");
+    const bool per_layer = cls >= AED_K_LN_QKV && cls <= AED_K_FFN2;
+    if (!per_layer && cls != AED_K_LN_VOCAB && cls != AED_K_CROSS_KV) return fail(d, AED_EINVAL, "kernel class cannot be timed alone");
+    const int cap = d->state == aed_decoder::CONSUMED ? d->last_prompt_len + d->last_max_new : d->host_pos;
+    StateArgs st = d->state_args(0, 0);
+    HIP_TRY(d, launch_prepare_timing(st, std::max(0, std::min(cap, d->cfg.max_dec_len) - 1), d->stream));
+    int n = 0;
+    HIP_TRY(d, hipEventRecord(d->t0, d->stream));
+    for (int r = 0; r < reps; ++r) {
+        if (cls == AED_K_LN_VOCAB) { HIP_TRY(d, k_ln_vocab(d)); ++n; continue; }
+        for (int l = 0; l < d->cfg.n_layers; ++l) { HIP_TRY(d, k_class(d, cls, l)); ++n; }
+    }
+    HIP_TRY(d, hipEventRecord(d->t1, d->stream));
+    HIP_TRY(d, hipEventSynchronize(d->t1));
+    HIP_TRY(d, hipEventElapsedTime(ms_total, d->t0, d->t1));
+    *launches = n;
+    return AED_OK;
+}
+
+aed_status aed_kernel_work(aed_decoder* d, int32_t cls, double* bytes, double* flops) {
+    if (!d) return AED_EINVAL;
+    if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
+    if (!bytes || !flops) return fail(d, AED_EINVAL, "NULL output");
+    HIP_TRY(d, hipStreamSynchronize(d->stream));
+    const double e = (double)d->esz, B = d->batch, dm = d->cfg.d_model, F = d->cfg.d_ffn, V = d->cfg.vocab;
+    auto gemm = [&](double M, double N, double K, double a_bytes, double out_bytes, double ln) {
+        *bytes = N * K * e + N * e + M * K * a_bytes + M * N * out_bytes + ln * 2 * K * e;
+        *flops = 2 * M * N * K;
+    };
+    switch (cls) {
+        case AED_K_LN_QKV: gemm(B, 3 * dm, dm, 4, 0, 1); *bytes += B * dm * 4 + 2 * B * dm * e; break;
+        case AED_K_SELF_OUT: case AED_K_CROSS_OUT: gemm(B, dm, dm, e, 8, 0); break;
+        case AED_K_LN_CROSSQ: gemm(B, dm, dm, 4, 4, 1); break;
+        case AED_K_LN_FFN1: gemm(B, F, dm, 4, e, 1); break;
+        case AED_K_FFN2: gemm(B, dm, F, e, 8, 0); break;
+        case AED_K_LN_VOCAB: gemm(B, V, dm, 4, 4, 1); break;
+        case AED_K_CROSS_KV: gemm((double)d->total_enc, 2 * dm, dm, e, e, 0); break;
+        case AED_K_SELF_ATTN: case AED_K_CROSS_ATTN: {
+            double keys = 0;
+            if (cls == AED_K_CROSS_ATTN) keys = (double)d->total_enc;
+            else {
+                std::vector<int> len(d->batch);
+                HIP_TRY(d, hipMemcpy(len.data(), d->at<int>(d->lay.seq_len), (size_t)d->batch * 4, hipMemcpyDeviceToHost));
+                for (int b = 0; b < d->batch; ++b) keys += std::min(len[b], d->cfg.max_dec_len - 1) + 1;
+            }
+            *bytes = keys * 2 * dm * e + B * dm * 4 + B * dm * e;
+            *flops = keys * 4 * dm;
+            break;
+        }
+        default: return fail(d, AED_EINVAL, "unknown kernel class");
+    }
+    return AED_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Host-side launch interface of the gfx950 kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aed {
+
+enum Dtype { kF32 = 0, kBF16 = 1 };
+constexpr int kPage = 16;  // tokens per self-attention KV page
+
+// ---------------------------------------------------------------- decode GEMM
+// C[M,N] = prologue(A)[M,K] . W[N,K]^T (+bias), then an epilogue.
+enum GemmPro { PRO_LN = 0, PRO_T = 1 };
+enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROSSKV = 4 };
+
+struct GemmArgs {
+    const void* A;        // PRO_LN: float [M,K] (residual stream); PRO_T: T [rows,K]
+    const int* a_row_map; // PRO_T only, may be null: A row of output row m is a_row_map[m]
+    const void* W;        // T [N,K]
+    const void* bias;     // T [N] or null
+    const void* ln_g;     // T [K]  (PRO_LN)
+    const void* ln_b;     // T [K]
+    float ln_eps;
+    int M, N, K;
+    void* out;            // EPI_RESID: float [M,N], += ; EPI_F32: float [M,N]; EPI_RELU_T: T [M,N];
+                          // EPI_QKV: float q [M,d_model]
+    // EPI_QKV: columns [d,2d) and [2d,3d) go to the paged self-attention cache of this layer
+    void* k_pool;         // T [pages][H][16][Dh]
+    void* v_pool;
+    const int* page_table;  // [batch][max_pages]
+    int max_pages;
+    const int* seq_len;     // position being written, per sequence
+    const int* finished;    // nonzero: do not append
+    int n_heads, head_dim, d_model;
+    // EPI_CROSSKV: columns [0,d) -> kc, [d,2d) -> vc, layout [H][t_cap][Dh]
+    void* kc;
+    void* vc;
+    long long t_cap;
+};
+
+// Returns hipSuccess or the launch error.  Requirements (checked by the caller):
+// K % 256 == 0, N % 64 == 0, PRO_LN: K <= 1024.
+hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------- decode attention
+struct AttnArgs {
+    const float* q;       // [B, d_model]
+    void* out;            // T [B, d_model]
+    const void* K;        // self: T [pages][H][16][Dh]; cross: T [H][t_cap][Dh]  (this layer)
+    const void* V;
+    const int* finished;  // [B]
+    // self
+    const int* page_table;
+    int max_pages;
+    const int* seq_len;   // keys = seq_len[b] + 1
+    int chunk;            // keys per work item, multiple of 64
+    int n_chunks_max;     // grid.z
+    int batch;
+    // cross
+    const int4* items;    // {b, key_start, n_keys, chunk_idx | n_chunks << 16}
+    int n_items;
+    const int* enc_off;   // [B+1] frame offsets in the packed layout
+    long long t_cap;
+    // split-K merge
+    float* part;          // [B*H][max_chunks][Dh+2]
+    int* counters;        // [B*H], zero between launches
+    int max_chunks;
+    int n_heads, head_dim;
+    float scale_log2e;    // log2(e) / sqrt(Dh)
+};
+hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------- small kernels
+struct StateArgs {
+    int* seq_len; int* n_gen; int* finished; int* cur_tok; int* limit; int* n_finished;
+    int* prompt;      // [B, prompt_stride]
+    int* out_tokens;  // [B, out_stride]
+    int prompt_len, prompt_stride, out_stride, max_new;
+    int eos_id, pad_id, batch, vocab;
+};
+// x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]
+hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,
+                        int d_model, int max_positions, float emb_scale, hipStream_t s);
+// greedy = 1: prompt feeding, argmax, EOS rules, output writes; greedy = 0: argmax only -> step_out (may be null)
+hipError_t launch_sample(const float* logits, const StateArgs& st, int greedy, int* step_out, hipStream_t s);
+// seq_len = n_gen = finished = 0, n_finished = 0, limit = limits ? limits[b] : INT_MAX, out_tokens = pad
+hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out, hipStream_t s);
+// cur_tok[b] = src[b * stride]
+hipError_t launch_set_tokens(int* cur_tok, const int* src, int stride, int batch, hipStream_t s);
+// out[b] = n_gen[b]; dst[b, t] = out_tokens[b, t]
+hipError_t launch_copy_out(const StateArgs& st, int* dst_tokens, int* dst_lens, hipStream_t s);
+
+// finished[b] = 0, seq_len[b] = clamp(seq_len[b], 0, max_pos): a valid mid-decode state for timing runs
+hipError_t launch_prepare_timing(const StateArgs& st, int max_pos, hipStream_t s);
+
+}  // namespace aed

@@ -1,0 +1,164 @@
+// Small kernels of the decoder step: token + position embedding, the greedy
+// sampler with its device-side sequence state, and state bookkeeping.
+//
+// All per-sequence state that changes from step to step (position, number of
+// generated tokens, finished flag, next input token) lives in device memory and
+// is advanced by the sampler, so one captured launch graph can be replayed for
+// every step without touching its arguments.
+#include <limits.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace aed {
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(float* __restrict__ x, const T* __restrict__ tok_emb,
+                                                    const T* __restrict__ pos_emb, StateArgs st, int d,
+                                                    int max_positions, float emb_scale) {
+    const int b = blockIdx.x;
+    int tok = st.cur_tok[b];
+    tok = tok < 0 ? 0 : (tok >= st.vocab ? st.vocab - 1 : tok);
+    int pos = st.seq_len[b];
+    pos = pos < max_positions ? pos : max_positions - 1;
+    const T* e = tok_emb + (size_t)tok * d;
+    const T* p = pos_emb + (size_t)pos * d;
+    for (int i = threadIdx.x * 4; i < d; i += 256 * 4) {
+        f32x4 ev = load4(e + i), pv = load4(p + i);
+        f32x4 o;
+        o[0] = emb_scale * ev[0] + pv[0];
+        o[1] = emb_scale * ev[1] + pv[1];
+        o[2] = emb_scale * ev[2] + pv[2];
+        o[3] = emb_scale * ev[3] + pv[3];
+        store4(x + (size_t)b * d + i, o);
+    }
+}
+
+hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,
+                        int d_model, int max_positions, float emb_scale, hipStream_t s) {
+    if (dt == kBF16)
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(st.batch), dim3(256), 0, s, x,
+                           static_cast<const bf16_t*>(tok_emb), static_cast<const bf16_t*>(pos_emb), st, d_model,
+                           max_positions, emb_scale);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(st.batch), dim3(256), 0, s, x,
+                           static_cast<const float*>(tok_emb), static_cast<const float*>(pos_emb), st, d_model,
+                           max_positions, emb_scale);
+    return hipGetLastError();
+}
+
+// argmax with the lowest index on ties: (value, index) pairs ordered by value
+// descending, then index ascending.
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
+
+__global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ logits, StateArgs st, int greedy,
+                                                     int* __restrict__ step_out) {
+    const int b = blockIdx.x, tid = threadIdx.x;
+    if (greedy && st.finished[b]) return;
+    const int pos = st.seq_len[b];
+    if (greedy && pos + 1 < st.prompt_len) {  // still feeding the prompt: no token is emitted
+        if (tid == 0) {
+            st.cur_tok[b] = st.prompt[(size_t)b * st.prompt_stride + pos + 1];
+            st.seq_len[b] = pos + 1;
+        }
+        return;
+    }
+    const float* row = logits + (size_t)b * st.vocab;
+    float bv = -INFINITY;
+    int bi = INT_MAX;
+    for (int i = tid; i < st.vocab; i += 256) {
+        const float v = row[i];
+        if (better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int oi = __shfl_xor(bi, off);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    if ((tid & 63) == 0) { sv[tid >> 6] = bv; si[tid >> 6] = bi; }
+    __syncthreads();
+    if (tid != 0) return;
+    for (int w = 1; w < 4; ++w)
+        if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+    int tok = bi == INT_MAX ? 0 : bi;
+    if (!greedy) {
+        if (step_out) step_out[b] = tok;
+        st.cur_tok[b] = tok;
+        st.seq_len[b] = pos + 1;
+        return;
+    }
+    const int n = st.n_gen[b];
+    if (n + 1 >= st.limit[b]) tok = st.eos_id;  // forced end at the per-sequence target length
+    st.out_tokens[(size_t)b * st.out_stride + n] = tok;
+    st.n_gen[b] = n + 1;
+    st.cur_tok[b] = tok;
+    st.seq_len[b] = pos + 1;
+    if ((st.eos_id >= 0 && tok == st.eos_id) || n + 1 >= st.max_new) {
+        st.finished[b] = 1;
+        atomicAdd(st.n_finished, 1);
+    }
+}
+
+hipError_t launch_sample(const float* logits, const StateArgs& st, int greedy, int* step_out, hipStream_t s) {
+    hipLaunchKernelGGL(sample_kernel, dim3(st.batch), dim3(256), 0, s, logits, st, greedy, step_out);
+    return hipGetLastError();
+}
+
+__global__ void reset_kernel(StateArgs st, const int* __restrict__ limits, int fill_out) {
+    const int b = blockIdx.x;
+    if (threadIdx.x == 0) {
+        st.seq_len[b] = 0;
+        st.n_gen[b] = 0;
+        st.finished[b] = 0;
+        st.cur_tok[b] = st.prompt ? st.prompt[(size_t)b * st.prompt_stride] : 0;
+        st.limit[b] = limits ? limits[b] : INT_MAX;
+        if (b == 0) *st.n_finished = 0;
+    }
+    if (fill_out)
+        for (int t = threadIdx.x; t < st.max_new; t += blockDim.x) st.out_tokens[(size_t)b * st.out_stride + t] = st.pad_id;
+}
+
+hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out, hipStream_t s) {
+    hipLaunchKernelGGL(reset_kernel, dim3(st.batch), dim3(64), 0, s, st, limits_dev, fill_out);
+    return hipGetLastError();
+}
+
+__global__ void set_tokens_kernel(int* __restrict__ cur_tok, const int* __restrict__ src, int stride, int batch) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) cur_tok[b] = src[(size_t)b * stride];
+}
+
+hipError_t launch_set_tokens(int* cur_tok, const int* src, int stride, int batch, hipStream_t s) {
+    hipLaunchKernelGGL(set_tokens_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, cur_tok, src, stride, batch);
+    return hipGetLastError();
+}
+
+__global__ void copy_out_kernel(StateArgs st, int* __restrict__ dst_tokens, int* __restrict__ dst_lens) {
+    const int b = blockIdx.x;
+    for (int t = threadIdx.x; t < st.max_new; t += blockDim.x)
+        dst_tokens[(size_t)b * st.max_new + t] = st.out_tokens[(size_t)b * st.out_stride + t];
+    if (threadIdx.x == 0) dst_lens[b] = st.n_gen[b];
+}
+
+hipError_t launch_copy_out(const StateArgs& st, int* dst_tokens, int* dst_lens, hipStream_t s) {
+    hipLaunchKernelGGL(copy_out_kernel, dim3(st.batch), dim3(64), 0, s, st, dst_tokens, dst_lens);
+    return hipGetLastError();
+}
+
+__global__ void prepare_timing_kernel(StateArgs st, int max_pos) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= st.batch) return;
+    st.finished[b] = 0;
+    const int p = st.seq_len[b];
+    st.seq_len[b] = p < 0 ? 0 : (p > max_pos ? max_pos : p);
+}
+
+hipError_t launch_prepare_timing(const StateArgs& st, int max_pos, hipStream_t s) {
+    hipLaunchKernelGGL(prepare_timing_kernel, dim3((st.batch + 255) / 256), dim3(256), 0, s, st, max_pos);
+    return hipGetLastError();
+}
+
+}  // namespace aed

@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Tolerances: fp32 mode 1e-4 absolute on logits,
+bf16 mode 3e-2; token ids identical wherever the oracle's top-1/top-2 margin
+exceeds twice the tolerance (otherwise one of the near-tied ids)."""
+import numpy as np
+import pytest
+
+from paper_2503_05931_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+def unit_workload(dtype, d_model, n_heads, head_dim, enc_lens, seed, n_layers=2, d_ffn=512, vocab=256,
+                  max_new=40, eos_id=-1, **kw):
+    cfg = W.DecoderConfig(name="unit", n_layers=n_layers, d_model=d_model, n_heads=n_heads, head_dim=head_dim,
+                          d_ffn=d_ffn, vocab=vocab, dtype=dtype, batch=len(enc_lens), prompt_len=4,
+                          max_new=max_new, eos_id=eos_id, **kw)
+    return W.custom(cfg, enc_lens, seed, random_ln=True)
+
+
+def random_tokens(cfg, B, S, seed):
+    return np.random.default_rng(seed).integers(0, cfg.vocab, size=(B, S)).astype(np.int32)
+
+
+# ---------------------------------------------------------------- tiny fp32 configuration
+def test_tiny_fp32_teacher_forced_and_greedy(torch_cuda, oracle):
+    from tests import gpu_util as G
+    wl = W.make("tiny")
+    cfg = wl.cfg
+    m = oracle.Model(cfg, wl.weights)
+    ref_toks, ref_lens, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, cfg.max_new, want_logits=True)
+    dec = G.make_decoder(wl)
+    # teacher-forced on the oracle's tokens
+    full = np.concatenate([wl.prompt, ref_toks[:, :-1]], axis=1)
+    glog, gids = G.forced_logits_gpu(dec, wl, full)
+    P = cfg.prompt_len
+    err, near = G.check_forced(ref_logits, glog[:, P - 1:], gids[:, P - 1:], G.TOL["fp32"])
+    print(f"tiny fp32: max |dlogit| = {err:.2e}, near-tie steps = {near}")
+    # cross K/V and the self cache against the oracle
+    for layer in (0, cfg.n_layers - 1):
+        for b in (0, len(wl.enc_lens) - 1):
+            sub = wl.subset([b])
+            Kr, Vr = m.cross_kv(layer, sub.enc)
+            Kg, Vg = dec.aed_read_cross_kv(layer, b, int(wl.enc_lens[b]))
+            assert np.abs(Kg - Kr).max() < 1e-4 and np.abs(Vg - Vr).max() < 1e-4
+            Ks, Vs = dec.aed_read_self_kv(layer, b)
+            assert Ks.shape[0] == full.shape[1] and np.isfinite(Ks).all() and np.isfinite(Vs).all()
+    # free-running greedy through the captured graph
+    torch = torch_cuda
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    toks, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), cfg.max_new)
+    toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+    assert (lens == cfg.max_new).all()
+    first = G.first_near_tie(ref_logits, G.TOL["fp32"])
+    for b in range(len(first)):
+        assert (toks[b, :first[b]] == ref_toks[b, :first[b]]).all()
+    print("tiny fp32: free-running ids identical up to step", first.tolist())
+    dec.close()
+
+
+# ---------------------------------------------------------------- shapes, ragged tails, page boundaries
+@pytest.mark.parametrize("dtype,d_model,n_heads,head_dim,enc_lens", [
+    ("fp32", 256, 4, 64, [1, 15, 16, 17, 63, 64, 65, 130]),
+    ("fp32", 256, 2, 128, [3, 200, 31]),
+    ("bf16", 256, 4, 64, [1, 15, 16, 17, 63, 64, 65, 130]),
+    ("bf16", 512, 4, 128, [1, 2, 129, 500, 77]),
+    ("bf16", 1024, 8, 128, [257, 1, 64]),
+    ("bf16", 768, 12, 64, [40]),
+])
+def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head_dim, enc_lens):
+    from tests import gpu_util as G
+    wl = unit_workload(dtype, d_model, n_heads, head_dim, enc_lens, seed=len(enc_lens) + d_model)
+    S = 35  # crosses the 16- and 32-token page boundaries
+    toks = random_tokens(wl.cfg, len(enc_lens), S, 5)
+    ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL[dtype])
+    print(f"{dtype} d={d_model} H={n_heads}x{head_dim}: max |dlogit| = {err:.2e}, near ties {near}")
+    # determinism: a second run is bit-identical
+    glog2, gids2 = G.forced_logits_gpu(dec, wl, toks)
+    assert (glog2 == glog).all() and (gids2 == gids).all()
+    # cached self K/V equal the oracle's k, v for the fed tokens (checked via the padded routine's
+    # agreement elsewhere; here: finite and of the right length)
+    Ks, Vs = dec.aed_read_self_kv(1, 0)
+    assert Ks.shape == (S, d_model) and np.isfinite(Ks).all() and np.isfinite(Vs).all()
+    dec.close()
+
+
+def test_split_chunks_and_capacity_slack(torch_cuda, oracle):
+    """Few long sequences: the work lists cut keys into several chunks per (sequence, head) and
+    the last-arriver merge runs; capacities larger than the batch leave unused slots poisoned."""
+    from tests import gpu_util as G
+    wl = unit_workload("bf16", 256, 4, 64, [500, 300], seed=77, max_new=140)
+    S = 140
+    toks = random_tokens(wl.cfg, 2, S, 6)
+    ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl, max_batch=5, max_total=1500, max_dec_len=160)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
+    print(f"split-K case: max |dlogit| = {err:.2e}")
+    dec.close()
+
+
+def test_padded_entry_point_equals_packed(torch_cuda, oracle):
+    from tests import gpu_util as G
+    torch = torch_cuda
+    wl = unit_workload("bf16", 256, 4, 64, [5, 33, 1, 18], seed=9)
+    toks = random_tokens(wl.cfg, 4, 6, 7)
+    dec = G.make_decoder(wl)
+    glog, _ = G.forced_logits_gpu(dec, wl, toks)
+    T_max = 40
+    pad = np.full((4, T_max, 256), np.nan, np.float32)   # poisoned padding rows
+    off = wl.enc_offsets
+    for b in range(4):
+        pad[b, :wl.enc_lens[b]] = wl.enc[off[b]:off[b + 1]]
+    dec.aed_cross_kv_precompute_padded(dec.to_device(pad), wl.enc_lens)
+    tok_dev = torch.from_numpy(np.ascontiguousarray(toks.T)).to(dec.device)
+    rows = []
+    for s in range(toks.shape[1]):
+        _, lg = dec.aed_decode_step(tok_dev[s].contiguous())
+        rows.append(lg)
+    plog = torch.stack(rows, 1).cpu().numpy().astype(np.float64)
+    assert np.isfinite(plog).all() and (plog == glog).all()
+    dec.close()
+
+
+# ---------------------------------------------------------------- greedy semantics on the device
+def test_greedy_eos_forced_eos_and_padding(torch_cuda, oracle):
+    from tests import gpu_util as G
+    torch = torch_cuda
+    wl0 = unit_workload("fp32", 256, 4, 64, [9, 30, 4, 17, 52], seed=21, max_new=24)
+    m0 = oracle.Model(wl0.cfg, wl0.weights)
+    free, _ = m0.greedy_decode(wl0.enc, wl0.enc_lens, wl0.prompt, 24)
+    eos = int(free[1, 5])                      # sequence 1 emits this id at step 5
+    wl = unit_workload("fp32", 256, 4, 64, [9, 30, 4, 17, 52], seed=21, max_new=24, eos_id=eos, pad_id=7)
+    m = oracle.Model(wl.cfg, wl.weights)
+    target = np.array([3, 24, 1, 12, 30], np.int32)
+    ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, 24, max_new_per_seq=target,
+                                               want_logits=True)
+    dec = G.make_decoder(wl)
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    toks, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), 24, max_new_per_seq=target)
+    toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+    first = G.first_near_tie(ref_logits[:, :], G.TOL["fp32"])
+    for b in range(5):
+        if first[b] >= ref_l[b]:               # no near-tie before this sequence ended: everything is fixed
+            assert lens[b] == ref_l[b]
+            assert (toks[b] == ref_t[b]).all()  # includes the pad_id tail
+    assert lens[2] == 1 and toks[2, 0] == eos and (toks[2, 1:] == 7).all()
+    assert (lens <= np.minimum(target, 24)).all()
+    # the same decoder, second call without per-sequence limits
+    ref_t2, ref_l2 = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, 24)
+    toks2, lens2 = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), 24)
+    for b in range(5):
+        if first[b] >= ref_l2[b]:
+            assert lens2.cpu().numpy()[b] == ref_l2[b] and (toks2.cpu().numpy()[b] == ref_t2[b]).all()
+    dec.close()
+
+
+def test_error_paths_on_device(torch_cuda):
+    from tests import gpu_util as G
+    from paper_2503_05931_amd import binding
+    torch = torch_cuda
+    wl = unit_workload("bf16", 256, 4, 64, [5, 6], seed=3, max_new=12)
+    dec = G.make_decoder(wl, max_batch=2, max_total=20, max_dec_len=16, kv_pages=3)
+    tok = torch.zeros(2, dtype=torch.int32, device=dec.device)
+    prompt = torch.from_numpy(wl.prompt).to(dec.device)
+
+    def status(fn):
+        with pytest.raises(binding.AedError) as ei:
+            fn()
+        return ei.value.status
+
+    dec.batch = 2
+    assert status(lambda: dec.aed_decode_step(tok)) == binding.AED_ESTATE
+    assert status(lambda: dec.aed_greedy_decode(prompt, 4)) == binding.AED_ESTATE
+    enc = dec.to_device(wl.enc)
+    assert status(lambda: dec.aed_cross_kv_precompute(enc, [5, 0])) == binding.AED_EINVAL
+    assert status(lambda: dec.aed_cross_kv_precompute(enc, [5, 6, 1])) == binding.AED_ECAPACITY
+    assert status(lambda: dec.aed_cross_kv_precompute(enc, [15, 6])) == binding.AED_ECAPACITY
+    dec.aed_cross_kv_precompute(enc, wl.enc_lens)
+    assert status(lambda: dec.aed_greedy_decode(prompt, 13)) == binding.AED_ECAPACITY      # 4 + 13 > 16
+    assert status(lambda: dec.aed_greedy_decode(prompt, 4, max_new_per_seq=[2, 2])) == binding.AED_EINVAL  # eos off
+    assert status(lambda: dec.aed_greedy_decode(prompt, 0)) == binding.AED_EINVAL
+    # page pool of 3 pages: two sequences need one page each for 16 positions, the 17th position has no page
+    for _ in range(16):
+        dec.aed_decode_step(tok, want_logits=False)
+    assert status(lambda: dec.aed_decode_step(tok)) == binding.AED_ECAPACITY
+    dec.aed_cross_kv_precompute(enc, wl.enc_lens)
+    toks, lens = dec.aed_greedy_decode(prompt, 12)          # still usable after the errors
+    assert (lens.cpu().numpy() == 12).all()
+    assert status(lambda: dec.aed_decode_step(tok)) == binding.AED_ESTATE   # greedy consumed the batch
+    dec.close()
+    # a pool too small for the batch
+    dec = G.make_decoder(wl, max_batch=2, max_total=20, max_dec_len=32, kv_pages=3)
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    assert status(lambda: dec.aed_greedy_decode(prompt, 20)) == binding.AED_ECAPACITY       # 2 x 2 pages > 3
+    dec.close()
