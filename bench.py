@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the autoregressive AED decoder path on one MI355X.
+
+A step = one pass of the whole path over one batch of seeded synthetic input:
+cross-attention K/V precompute for all layers, then greedy decoding of the
+4-token prompt plus max_new tokens through the captured launch graph.  Inputs
+(weights, encoder states, prompts) are resident in HBM before the timed region.
+Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def run_workload(name, steps, warmup, want_roofline):
+    import numpy as np
+    import torch
+    from paper_2503_05931_amd import binding, workloads as W
+
+    wl = W.make(name)
+    cfg = wl.cfg
+    B = cfg.batch
+    dec = binding.Decoder(cfg, wl.weights, max_batch=B, max_total_enc_frames=int(wl.enc_lens.sum()),
+                          max_dec_len=cfg.max_dec_len)
+    enc = dec.to_device(wl.enc)
+    prompt = torch.from_numpy(wl.prompt).to(dec.device)
+    out_tokens = torch.empty((B, cfg.max_new), dtype=torch.int32, device=dec.device)
+    out_lens = torch.empty(B, dtype=torch.int32, device=dec.device)
+    mnps = wl.max_new_per_seq
+    torch.cuda.synchronize()
+
+    def one_step():
+        dec.aed_cross_kv_precompute(enc, wl.enc_lens)
+        dec.aed_greedy_decode(prompt, cfg.max_new, max_new_per_seq=mnps, out_tokens=out_tokens, out_lens=out_lens)
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tokens = int(out_lens.sum().item())
+    res = {
+        "workload": name,
+        "tokens_per_step": tokens,
+        "ms_per_step": 1e3 * dt / steps,
+        "tokens_per_s": tokens * steps / dt,
+    }
+    # decode alone (cross K/V already resident), and the precompute alone
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    dec.aed_cross_kv_precompute(enc, wl.enc_lens)
+    torch.cuda.synchronize()
+    res["precompute_ms"] = 1e3 * (time.perf_counter() - t0)
+    t0 = time.perf_counter()
+    dec.aed_greedy_decode(prompt, cfg.max_new, max_new_per_seq=mnps, out_tokens=out_tokens, out_lens=out_lens)
+    torch.cuda.synchronize()
+    d2 = time.perf_counter() - t0
+    res["decode_only_tokens_per_s"] = tokens / d2
+    res["decode_ms_per_token_step"] = 1e3 * d2 / (cfg.prompt_len - 1 + cfg.max_new)
+    if wl.durations_s is not None:
+        res["decoder_rtfx"] = float(np.sum(wl.durations_s)) * steps / dt
+
+    if want_roofline:
+        # Per-kernel-class time at the middle of the decode: run half of the steps, then replay each
+        # class over all layers between HIP events on the decoder's stream.
+        dec.aed_cross_kv_precompute(enc, wl.enc_lens)
+        half = max(1, cfg.max_new // 2)
+        dec.aed_greedy_decode(prompt, half)
+        classes = [binding.K_LN_QKV, binding.K_SELF_ATTN, binding.K_SELF_OUT, binding.K_LN_CROSSQ,
+                   binding.K_CROSS_ATTN, binding.K_CROSS_OUT, binding.K_LN_FFN1, binding.K_FFN2]
+        per = {}
+        for k in classes:
+            dec.aed_time_kernels(k, 2)  # warm
+            ms, n = dec.aed_time_kernels(k, 20)
+            nbytes, flops = dec.aed_kernel_work(k)
+            per[binding.KERNEL_NAMES[k]] = {"us": 1e3 * ms / n, "bytes": nbytes, "flops": flops,
+                                            "GBps": nbytes / (ms / n * 1e-3) / 1e9}
+        dom = max(per, key=lambda k: per[k]["us"])
+        p = per[dom]
+        res["kernels"] = {k: {"us": round(v["us"], 2), "GBps": round(v["GBps"], 1)} for k, v in per.items()}
+        res["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": p["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": p["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                           "avg_launch_us": p["us"], "algorithmic_bytes_per_launch": p["bytes"]}
+    dec.close()
+    return res, wl
+
+
+def cpu_baseline(wl, n_seq=8, n_new=16):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import aed_oracle as O
+    sub = wl.subset(list(range(min(n_seq, len(wl.enc_lens)))))
+    m = O.Model(wl.cfg, wl.weights)
+    t0 = time.perf_counter()
+    m.greedy_decode(sub.enc, sub.enc_lens, sub.prompt, n_new)
+    dt = time.perf_counter() - t0
+    B = len(sub.enc_lens)
+    return {"value": B * n_new / dt, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"first {B} sequences of the workload, cross K/V precompute + {wl.cfg.prompt_len}-token prompt "
+                      f"+ {n_new} greedy tokens each ({dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="canary24_b64")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true", help="skip the 4-layer decoder's extra line")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the decoder shards by sequence with no exchange between GPUs, "
+              "and this build runs on a single MI355X; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
+        sys.exit(1)
+
+    res, wl = run_workload(args.workload, args.steps, args.warmup, want_roofline=True)
+    cfg = wl.cfg
+    line = {
+        "metric": "decoded tokens/sec at 1 MI355X (24L and 4L decoder) + % HBM/MFMA roofline",
+        "value": res["tokens_per_s"],
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": args.workload, "n_layers": cfg.n_layers, "d_model": cfg.d_model,
+                   "batch": cfg.batch, "prompt_len": cfg.prompt_len, "max_new": cfg.max_new,
+                   "enc_frames_total": int(wl.enc_lens.sum()),
+                   "step": "cross K/V precompute + greedy decode of the batch"},
+        "decode_only_tokens_per_s": res["decode_only_tokens_per_s"],
+        "decode_ms_per_token_step": res["decode_ms_per_token_step"],
+        "precompute_ms": res["precompute_ms"],
+        "decoder_rtfx": res.get("decoder_rtfx"),
+        "kernels": res.get("kernels"),
+        "roofline": res.get("roofline"),
+    }
+    if not args.no_also and args.workload == "canary24_b64":
+        r4, _ = run_workload("flash4_b256", args.steps, args.warmup, want_roofline=False)
+        line["also"] = [{"workload": "flash4_b256", "n_layers": 4, "batch": 256, "value": r4["tokens_per_s"],
+                         "unit": "tokens/s", "ms_per_step": r4["ms_per_step"],
+                         "decode_only_tokens_per_s": r4["decode_only_tokens_per_s"],
+                         "decoder_rtfx": r4.get("decoder_rtfx")}]
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -19,7 +19,8 @@ using namespace aed;
 namespace {
 
 constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
-constexpr int kTargetItems = 768;   // work items aimed at per attention launch (3 per CU)
+constexpr int kTargetItems = 512;   // work items aimed at per attention launch when sequences are cut
+constexpr int kMinItemsNoSplit = 128;  // batch * heads from which sequences are never cut
 
 thread_local std::string g_create_error;
 
@@ -29,8 +30,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     size_t x, q, logits, attn_out, ffn_h;
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished;
-    size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part, counters;
-    size_t k_pool, v_pool, kc, vc;
+    size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part;
+    size_t k_pool, v_pool, kc, vc, w_frag;
     size_t total;
     int max_pages, n_pages, max_items;
     size_t pool_layer_elems, cross_layer_elems;
@@ -64,6 +65,7 @@ aed_status check_config(const aed_config* c, std::string& err) {
 void make_layout(const aed_config* c, Layout* L) {
     const size_t e = c->dtype == 1 ? 2 : 4;
     const size_t B = c->max_batch, d = c->d_model, H = c->n_heads, Dh = c->head_dim;
+    const size_t Bp = align_up(B, 64);  // fragment-order activations are read in whole 64-row tiles
     L->max_pages = (c->max_dec_len + kPage - 1) / kPage;
     L->n_pages = c->kv_pages > 0 ? c->kv_pages : (int)(B * L->max_pages);
     L->max_items = c->max_total_enc_frames / 64 + c->max_batch;
@@ -71,11 +73,11 @@ void make_layout(const aed_config* c, Layout* L) {
     L->cross_layer_elems = (size_t)c->max_total_enc_frames * d;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    L->x = take(B * d * 4);
+    L->x = take(Bp * d * 4);
     L->q = take(B * d * 4);
     L->logits = take(B * (size_t)c->vocab * 4);
-    L->attn_out = take(B * d * e);
-    L->ffn_h = take(B * (size_t)c->d_ffn * e);
+    L->attn_out = take(Bp * d * e);
+    L->ffn_h = take(Bp * (size_t)c->d_ffn * e);
     L->seq_len = take(B * 4);
     L->n_gen = take(B * 4);
     L->finished = take(B * 4);
@@ -90,11 +92,12 @@ void make_layout(const aed_config* c, Layout* L) {
     L->row_map = take((size_t)c->max_total_enc_frames * 4);
     L->items = take((size_t)L->max_items * 16);
     L->part = take(B * H * kMaxChunks * (Dh + 2) * 4);
-    L->counters = take(B * H * 4);
     L->k_pool = take(L->pool_layer_elems * c->n_layers * e);
     L->v_pool = take(L->pool_layer_elems * c->n_layers * e);
     L->kc = take(L->cross_layer_elems * c->n_layers * e);
     L->vc = take(L->cross_layer_elems * c->n_layers * e);
+    // every weight matrix once more, in MFMA fragment order
+    L->w_frag = take(((size_t)c->n_layers * (8 * d * d + 2 * d * (size_t)c->d_ffn) + (size_t)c->vocab * d) * e);
     L->total = off;
 }
 
@@ -113,8 +116,11 @@ struct aed_decoder {
     Dtype dt;
     size_t esz;
     Layout lay;
-    std::vector<aed_layer_weights> layers;
+    std::vector<aed_layer_weights> layers;  // caller's pointers (biases, LayerNorm, embeddings are used in place)
     aed_weights w;
+    struct FragWeights { const void *w_qkv, *w_o, *w_cq, *w_ckv, *w_co, *w_ff1, *w_ff2; };
+    std::vector<FragWeights> fw;            // the matrices re-ordered into fragment order (workspace)
+    const void* fw_out = nullptr;
     hipStream_t stream;
     char* ws;
     // host-side state
@@ -123,7 +129,7 @@ struct aed_decoder {
     int host_pos = 0;     // positions fed so far (step API)
     int pages_used = 0;
     int n_items = 0;
-    int self_chunk = 64, self_nchunks = 1;
+    int self_chunk = 64, self_nchunks = 1, cross_chunk = 64;
     int last_prompt_len = 0, last_max_new = 0;
     long long total_enc = 0;
     const void* last_enc = nullptr;
@@ -177,14 +183,17 @@ aed_status fail(aed_decoder* d, aed_status st, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(d, AED_EHIP, "%s: %s", #expr, hipGetErrorString(e_));  \
     } while (0)
 
-// Keys per attention work item: enough items to occupy the GPU, at least 64
-// keys each, at most kMaxChunks items per (sequence, head).
-int pick_chunk(long long total_keys, int max_len, int n_heads) {
+// Keys per attention work item.  One workgroup per (sequence, head) streams at
+// most a few hundred keys, so sequences are cut into chunks only when
+// batch * heads leaves most of the 256 CUs idle; then the chunk aims at
+// kTargetItems items, at least 64 keys each, at most kMaxChunks per sequence.
+int pick_chunk(long long total_keys, int max_len, int batch, int n_heads) {
+    const long long whole = std::max<long long>(64, ((long long)max_len + 63) / 64 * 64);
+    if ((long long)batch * n_heads >= kMinItemsNoSplit) return (int)whole;
     long long c = (total_keys * n_heads + kTargetItems - 1) / kTargetItems;
-    long long lo = ((long long)max_len + kMaxChunks - 1) / kMaxChunks;
-    c = std::max(c, lo);
+    c = std::max(c, ((long long)max_len + kMaxChunks - 1) / kMaxChunks);
     c = std::max<long long>(64, (c + 63) / 64 * 64);
-    return (int)std::min<long long>(c, 1 << 20);
+    return (int)std::min(c, whole);
 }
 
 // ---------------------------------------------------------------- kernel argument builders
@@ -203,7 +212,7 @@ hipError_t k_ln_qkv(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d);
     g.A = d->at<float>(d->lay.x);
-    g.W = w.w_qkv; g.bias = w.b_qkv; g.ln_g = w.ln1_g; g.ln_b = w.ln1_b;
+    g.W = d->fw[l].w_qkv; g.bias = w.b_qkv; g.ln_g = w.ln1_g; g.ln_b = w.ln1_b;
     g.N = 3 * d->cfg.d_model; g.K = d->cfg.d_model;
     g.out = d->at<float>(d->lay.q);
     g.k_pool = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
@@ -222,7 +231,6 @@ AttnArgs attn_base(const aed_decoder* d) {
     a.out = d->ws + d->lay.attn_out;
     a.finished = d->at<int>(d->lay.finished);
     a.part = d->at<float>(d->lay.part);
-    a.counters = d->at<int>(d->lay.counters);
     a.max_chunks = kMaxChunks;
     a.n_heads = d->cfg.n_heads;
     a.head_dim = d->cfg.head_dim;
@@ -255,7 +263,7 @@ hipError_t k_ln_crossq(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d);
     g.A = d->at<float>(d->lay.x);
-    g.W = w.w_cq; g.bias = w.b_cq; g.ln_g = w.ln2_g; g.ln_b = w.ln2_b;
+    g.W = d->fw[l].w_cq; g.bias = w.b_cq; g.ln_g = w.ln2_g; g.ln_b = w.ln2_b;
     g.N = d->cfg.d_model; g.K = d->cfg.d_model;
     g.out = d->at<float>(d->lay.q);
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
@@ -268,6 +276,7 @@ hipError_t k_cross_attn(aed_decoder* d, int l) {
     a.items = d->at<int4>(d->lay.items);
     a.n_items = d->n_items;
     a.enc_off = d->at<int>(d->lay.enc_off);
+    a.chunk = d->cross_chunk;
     a.t_cap = d->cfg.max_total_enc_frames;
     return launch_attn_cross(d->dt, a, d->stream);
 }
@@ -276,7 +285,7 @@ hipError_t k_ln_ffn1(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d);
     g.A = d->at<float>(d->lay.x);
-    g.W = w.w_ff1; g.bias = w.b_ff1; g.ln_g = w.ln3_g; g.ln_b = w.ln3_b;
+    g.W = d->fw[l].w_ff1; g.bias = w.b_ff1; g.ln_g = w.ln3_g; g.ln_b = w.ln3_b;
     g.N = d->cfg.d_ffn; g.K = d->cfg.d_model;
     g.out = d->ws + d->lay.ffn_h;
     return launch_gemm(d->dt, PRO_LN, EPI_RELU_T, g, d->stream);
@@ -285,7 +294,7 @@ hipError_t k_ln_ffn1(aed_decoder* d, int l) {
 hipError_t k_ln_vocab(aed_decoder* d) {
     GemmArgs g = gemm_base(d);
     g.A = d->at<float>(d->lay.x);
-    g.W = d->w.w_out; g.bias = d->w.b_out; g.ln_g = d->w.lnf_g; g.ln_b = d->w.lnf_b;
+    g.W = d->fw_out; g.bias = d->w.b_out; g.ln_g = d->w.lnf_g; g.ln_b = d->w.lnf_b;
     g.N = d->cfg.vocab; g.K = d->cfg.d_model;
     g.out = d->at<float>(d->lay.logits);
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
@@ -296,12 +305,12 @@ hipError_t k_cross_kv(aed_decoder* d, int l) {
     GemmArgs g = gemm_base(d);
     g.A = d->last_enc;
     g.a_row_map = d->last_enc_padded ? d->at<int>(d->lay.row_map) : nullptr;
-    g.W = w.w_ckv; g.bias = w.b_ckv;
+    g.W = d->fw[l].w_ckv; g.bias = w.b_ckv;
     g.M = (int)d->total_enc; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
     g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.t_cap = d->cfg.max_total_enc_frames;
-    return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);
+    return launch_gemm(d->dt, PRO_RM, EPI_CROSSKV, g, d->stream);
 }
 
 hipError_t k_class(aed_decoder* d, int cls, int l) {
@@ -309,12 +318,12 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
     switch (cls) {
         case AED_K_LN_QKV: return k_ln_qkv(d, l);
         case AED_K_SELF_ATTN: return k_self_attn(d, l);
-        case AED_K_SELF_OUT: return k_resid(d, d->ws + d->lay.attn_out, w.w_o, w.b_o, d->cfg.d_model);
+        case AED_K_SELF_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model);
         case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
         case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
-        case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, w.w_co, w.b_co, d->cfg.d_model);
+        case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model);
         case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
-        case AED_K_FFN2: return k_resid(d, d->ws + d->lay.ffn_h, w.w_ff2, w.b_ff2, d->cfg.d_ffn);
+        case AED_K_FFN2: return k_resid(d, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn);
         case AED_K_CROSS_KV: return k_cross_kv(d, l);
         default: return hipErrorInvalidValue;
     }
@@ -366,7 +375,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     // host tables: frame offsets, cross-attention work list, optional row map
     std::vector<int> off(batch + 1, 0);
     for (int b = 0; b < batch; ++b) off[b + 1] = off[b] + enc_lens[b];
-    const int chunk = pick_chunk(total, max_len, d->cfg.n_heads);
+    const int chunk = pick_chunk(total, max_len, batch, d->cfg.n_heads);
     std::vector<int4> items;
     for (int b = 0; b < batch; ++b) {
         const int nc = (enc_lens[b] + chunk - 1) / chunk;
@@ -389,6 +398,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     }
     d->batch = batch;
     d->n_items = (int)items.size();
+    d->cross_chunk = chunk;
     d->total_enc = total;
     d->last_enc = enc;
     d->last_enc_padded = padded;
@@ -397,7 +407,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     d->host_pos = 0;
     d->pages_used = 0;
     d->page_table.assign((size_t)batch * d->lay.max_pages, 0);
-    d->self_chunk = pick_chunk((long long)batch * d->cfg.max_dec_len, d->cfg.max_dec_len, d->cfg.n_heads);
+    d->self_chunk = pick_chunk((long long)batch * d->cfg.max_dec_len, d->cfg.max_dec_len, batch, d->cfg.n_heads);
     d->self_nchunks = (d->cfg.max_dec_len + d->self_chunk - 1) / d->self_chunk;
     d->state = aed_decoder::NO_BATCH;
 
@@ -470,9 +480,32 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
             return cleanup(e, "hipEventCreate");
     if ((e = hipEventCreate(&d->t0)) != hipSuccess) return cleanup(e, "hipEventCreate");
     if ((e = hipEventCreate(&d->t1)) != hipSuccess) return cleanup(e, "hipEventCreate");
-    // counters of the split-K merge start at zero and return to zero after every launch
-    if ((e = hipMemsetAsync(d->ws + L.counters, 0, (size_t)cfg->max_batch * cfg->n_heads * 4, d->stream)) != hipSuccess)
-        return cleanup(e, "hipMemsetAsync");
+    // re-order every weight matrix into fragment order, once
+    {
+        char* p = d->ws + L.w_frag;
+        const int dm = cfg->d_model, F = cfg->d_ffn;
+        auto put = [&](const void* src, int N, int K) -> const void* {
+            void* dst = p;
+            if (e == hipSuccess) e = launch_reorder_weight(d->dt, src, dst, N, K, d->stream);
+            p += (size_t)N * K * d->esz;
+            return dst;
+        };
+        e = hipSuccess;
+        d->fw.resize(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            const aed_layer_weights& x = d->layers[l];
+            aed_decoder::FragWeights& f = d->fw[l];
+            f.w_qkv = put(x.w_qkv, 3 * dm, dm);
+            f.w_o = put(x.w_o, dm, dm);
+            f.w_cq = put(x.w_cq, dm, dm);
+            f.w_ckv = put(x.w_ckv, 2 * dm, dm);
+            f.w_co = put(x.w_co, dm, dm);
+            f.w_ff1 = put(x.w_ff1, F, dm);
+            f.w_ff2 = put(x.w_ff2, dm, F);
+        }
+        d->fw_out = put(d->w.w_out, cfg->vocab, dm);
+        if (e != hipSuccess) return cleanup(e, "weight re-ordering");
+    }
     if ((e = hipStreamSynchronize(d->stream)) != hipSuccess) return cleanup(e, "hipStreamSynchronize");
     *out = d;
     return AED_OK;
@@ -570,7 +603,7 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
                                   d->stream));
     HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.prompt_buf), prompt, (size_t)B * prompt_len * 4,
                               hipMemcpyDeviceToDevice, d->stream));
-    d->self_chunk = pick_chunk((long long)B * total_len, total_len, d->cfg.n_heads);
+    d->self_chunk = pick_chunk((long long)B * total_len, total_len, B, d->cfg.n_heads);
     d->self_nchunks = (total_len + d->self_chunk - 1) / d->self_chunk;
     d->last_prompt_len = prompt_len;
     d->last_max_new = max_new;

@@ -16,11 +16,13 @@
 // each instruction covers 4 whole rows (1 KB for bf16 head_dim 128).  The dot
 // products are reduced over the 16 lanes of a DPP row, the running softmax
 // (max, sum, weighted values) is kept per wavefront in base-2 exponent form,
-// the four wavefronts are merged through LDS, and chunks of the same
-// (sequence, head) are merged by the last workgroup to finish: partial
-// (max, sum, values) go to a scratch buffer, a counter per (sequence, head)
-// tells which workgroup is last, and that one combines the partials in chunk
-// order, so the result does not depend on scheduling.
+// the four wavefronts are merged through LDS.  Sequences of this workload are
+// short (at most 500 encoder frames, a few hundred decoded tokens), so one
+// workgroup per (sequence, head) is the normal case; only when the batch is too
+// small to occupy the GPU are long sequences cut into chunks, whose partial
+// (max, sum, values) go to a scratch buffer and are combined in chunk order by
+// a small second kernel (a kernel boundary is far cheaper here than
+// device-scope fences inside the kernel, which write back and invalidate L2).
 #include "common.h"
 #include "kernels.h"
 
@@ -124,7 +126,6 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
 
     __shared__ float sm_acc[4][DH];
     __shared__ float sm_m[4], sm_l[4];
-    __shared__ int sm_last;
     if (g == 0) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) sm_acc[wave][r * EPL + e] = acc[e];
@@ -141,27 +142,32 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
         l_tot += sm_l[w] * f;
         if (tid < DH) o += sm_acc[w][tid] * f;
     }
-    T* __restrict__ out = static_cast<T*>(a.out) + (size_t)b * H * DH + h * DH;
-    if (n_chunks == 1) {
-        if (tid < DH) out[tid] = from_f32<T>(o / l_tot);
+    if (n_chunks == 1) {  // the output feeds the next GEMM: fragment order
+        if (tid < DH)
+            *reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + tid, H * DH)) =
+                from_f32<T>(o / l_tot);
         return;
     }
 
-    // ---- several chunks: publish the partial, the last workgroup to arrive merges ----
-    const int bh = b * H + h;
-    float* __restrict__ my = a.part + ((size_t)bh * a.max_chunks + chunk_idx) * (DH + 2);
+    // ---- several chunks: publish the partial; attn_merge_kernel combines them in chunk order ----
+    float* __restrict__ my = a.part + ((size_t)(b * H + h) * a.max_chunks + chunk_idx) * (DH + 2);
     if (tid < DH) my[tid] = o;
     if (tid == 0) { my[DH] = m_tot; my[DH + 1] = l_tot; }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const int old = atomicAdd(&a.counters[bh], 1);
-        sm_last = (old == n_chunks - 1);
-    }
-    __syncthreads();
-    if (!sm_last) return;
-    __threadfence();
-    const float* __restrict__ base = a.part + (size_t)bh * a.max_chunks * (DH + 2);
+}
+
+// Combines the partial results of the chunks of one (sequence, head) in chunk
+// order (so the result does not depend on scheduling) -- launched only when a
+// launch shape cuts some sequence into more than one chunk.
+template <typename T, int DH, bool SELF>
+__global__ __launch_bounds__(DH) void attn_merge_kernel(AttnArgs a) {
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, H = a.n_heads;
+    if (a.finished[b]) return;
+    int total;
+    if constexpr (SELF) total = a.seq_len[b] + 1;
+    else total = a.enc_off[b + 1] - a.enc_off[b];
+    const int n_chunks = (total + a.chunk - 1) / a.chunk;
+    if (n_chunks <= 1) return;  // the attention kernel wrote the final result itself
+    const float* __restrict__ base = a.part + (size_t)(b * H + h) * a.max_chunks * (DH + 2);
     float M = -INFINITY;
     for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, base[(size_t)c * (DH + 2) + DH]);
     float L = 0.f, O = 0.f;
@@ -169,20 +175,24 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
         const float* pc = base + (size_t)c * (DH + 2);
         const float f = __builtin_amdgcn_exp2f(pc[DH] - M);
         L += pc[DH + 1] * f;
-        if (tid < DH) O += pc[tid] * f;
+        O += pc[tid] * f;
     }
-    if (tid < DH) out[tid] = from_f32<T>(O / L);
-    if (tid == 0) a.counters[bh] = 0;  // ready for the next launch
+    *reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + tid, H * DH)) =
+        from_f32<T>(O / L);
 }
 
 template <typename T, bool SELF>
-static hipError_t launch_dh(const AttnArgs& a, dim3 grid, hipStream_t s) {
-    if (a.head_dim == 128)
+static hipError_t launch_dh(const AttnArgs& a, dim3 grid, bool merge, hipStream_t s) {
+    dim3 mgrid(a.n_heads, a.batch);
+    if (a.head_dim == 128) {
         hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF>), grid, dim3(256), 0, s, a);
-    else if (a.head_dim == 64)
+        if (merge) hipLaunchKernelGGL((attn_merge_kernel<T, 128, SELF>), mgrid, dim3(128), 0, s, a);
+    } else if (a.head_dim == 64) {
         hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF>), grid, dim3(256), 0, s, a);
-    else
+        if (merge) hipLaunchKernelGGL((attn_merge_kernel<T, 64, SELF>), mgrid, dim3(64), 0, s, a);
+    } else {
         return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
@@ -190,13 +200,15 @@ hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s) {
     if (a.chunk < 64 || a.chunk % 64 != 0 || a.n_chunks_max < 1 || a.n_chunks_max > a.max_chunks)
         return hipErrorInvalidValue;
     dim3 grid(a.n_heads, a.batch, a.n_chunks_max);
-    return dt == kBF16 ? launch_dh<bf16_t, true>(a, grid, s) : launch_dh<float, true>(a, grid, s);
+    const bool merge = a.n_chunks_max > 1;
+    return dt == kBF16 ? launch_dh<bf16_t, true>(a, grid, merge, s) : launch_dh<float, true>(a, grid, merge, s);
 }
 
 hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s) {
-    if (a.n_items < 1) return hipErrorInvalidValue;
+    if (a.n_items < 1 || a.chunk < 64 || a.chunk % 64 != 0) return hipErrorInvalidValue;
     dim3 grid(a.n_heads, a.n_items);
-    return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, s) : launch_dh<float, false>(a, grid, s);
+    const bool merge = a.n_items > a.batch;
+    return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, merge, s) : launch_dh<float, false>(a, grid, merge, s);
 }
 
 }  // namespace aed

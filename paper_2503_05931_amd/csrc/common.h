@@ -64,6 +64,25 @@ __device__ __forceinline__ f32x4 load4(const bf16_t* p) {
     return o;
 }
 
+// ---- fragment layout ----
+// A [rows, K] matrix whose rows feed 16x16 MFMA tiles is kept in "fragment
+// order": 16-row x 64-k blocks, and inside a block the 16 consecutive k values
+// that lane l = 16 * ((k % 64) / 16) + row % 16 holds for the MFMA, cut into
+// 16-byte pieces, piece-major: block[(piece j)][lane l][16 bytes].  A wavefront
+// then loads piece j of a block with one fully coalesced 1 KB instruction.
+// ES = element size in bytes (2: bf16, 4: fp32); a lane's 16 elements are ES pieces.
+template <int ES> __host__ __device__ __forceinline__ size_t frag_block_bytes() { return (size_t)ES * 1024; }
+// byte offset of block (row tile rt, k block kb)
+template <int ES> __host__ __device__ __forceinline__ size_t frag_block_off(int rt, int kb, int K) {
+    return ((size_t)rt * (K >> 6) + kb) * ES * 1024;
+}
+// byte offset of element (row, k)
+template <int ES> __host__ __device__ __forceinline__ size_t frag_elem_off(int row, int k, int K) {
+    constexpr int EPP = 16 / ES;  // elements per 16-byte piece
+    const int e = k & 15, lane = ((k & 63) >> 4) * 16 + (row & 15);
+    return frag_block_off<ES>(row >> 4, k >> 6, K) + ((size_t)(e / EPP) * 64 + lane) * 16 + (size_t)(e % EPP) * ES;
+}
+
 // ---- sum over the 16 lanes of a DPP row (lanes 16k..16k+15); every lane gets the total ----
 template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));

@@ -8,14 +8,18 @@
 //   * the four wavefronts split K: wavefront w takes the 64-wide k blocks
 //     w, w+4, w+8, ..., and the partial tiles are summed through LDS in a
 //     fixed order (deterministic);
-//   * operands go from global memory straight into MFMA register layout with
-//     16-byte loads -- lane (r, g) (r = lane % 16, g = lane / 16) holds, for
-//     row r of a 16-row operand, the 16 consecutive k values k0 + 16 g .. +15
-//     of a 64-wide block.  Both operands use the same k assignment, so the
-//     MFMA's internal k order does not matter;
+//   * lane (r, g) (r = lane % 16, g = lane / 16) holds, for row r of a 16-row
+//     operand, the 16 consecutive k values k0 + 16 g .. +15 of a 64-wide block.
+//     Both operands use the same k assignment, so the MFMA's internal k order
+//     does not matter;
+//   * both operands live in memory in fragment order (common.h): the weights
+//     are re-ordered once when the decoder is created, the activations are
+//     written in that order by the kernels that produce them.  Every operand
+//     load is then one coalesced 1 KB instruction per wavefront straight into
+//     MFMA registers -- no LDS staging, no transposes;
 //   * the weight fragment is the first MFMA operand: lane (r, g) then holds
 //     C[m = r][n = 4 g .. 4 g + 3], four consecutive outputs of one row, which
-//     stores as one 16-byte (fp32) or 8-byte (bf16) vector.
+//     is one 16-byte (fp32) or 8-byte (bf16) store, also into fragment order.
 // The LayerNorm prologue keeps a wavefront's slice of the fp32 residual rows
 // in registers, gets the row statistics with two LDS exchanges (mean, then
 // centred sum of squares) and normalises in place, so the rows are read once.
@@ -28,13 +32,32 @@ template <typename T> struct Frag16;
 template <> struct Frag16<bf16_t> { bf16x8 lo, hi; };
 template <> struct Frag16<float> { float v[16]; };
 
-__device__ __forceinline__ Frag16<bf16_t> load_frag(const bf16_t* p) {
+// a lane's 16 k-values of one block in fragment order: pieces at stride 1 KB
+__device__ __forceinline__ Frag16<bf16_t> load_frag(const bf16_t* blk, int lane) {
+    Frag16<bf16_t> f;
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(blk) + lane;
+    f.lo = p[0];
+    f.hi = p[64];
+    return f;
+}
+__device__ __forceinline__ Frag16<float> load_frag(const float* blk, int lane) {
+    Frag16<float> f;
+    const f32x4* p = reinterpret_cast<const f32x4*>(blk) + lane;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f32x4 v = p[64 * j];
+        f.v[4 * j + 0] = v[0]; f.v[4 * j + 1] = v[1]; f.v[4 * j + 2] = v[2]; f.v[4 * j + 3] = v[3];
+    }
+    return f;
+}
+// row-major source: 16 consecutive elements
+__device__ __forceinline__ Frag16<bf16_t> load_frag_rm(const bf16_t* p) {
     Frag16<bf16_t> f;
     f.lo = reinterpret_cast<const bf16x8*>(p)[0];
     f.hi = reinterpret_cast<const bf16x8*>(p)[1];
     return f;
 }
-__device__ __forceinline__ Frag16<float> load_frag(const float* p) {
+__device__ __forceinline__ Frag16<float> load_frag_rm(const float* p) {
     Frag16<float> f;
     load_f32<16>(p, f.v);
     return f;
@@ -62,11 +85,13 @@ constexpr int kMaxLnBlocks = 4;  // PRO_LN: K <= 4 waves * 4 blocks * 64 = 1024
 template <typename T, int PRO, int EPI, int MT, int NT>
 __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
     constexpr int BM = 16 * MT, BN = 16 * NT;
+    constexpr int EP = (MT * NT * 64 + 255) / 256;  // output 4-vectors per thread in the epilogue
+    constexpr int ES = sizeof(T);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const int K = a.K, M = a.M;
     const int nblk = K >> 8;  // 64-wide k blocks per wavefront
-    const T* __restrict__ W = static_cast<const T*>(a.W);
+    const char* __restrict__ W = static_cast<const char*>(a.W);
 
     __shared__ f32x4 part[4][MT * NT][64];
     __shared__ float red[2][4][BM];
@@ -77,25 +102,45 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const T* wrow[NT];
+    // block (n tile, k block i*4 + wave) of the re-ordered weights
+    auto wblk = [&](int nt, int i) {
+        return reinterpret_cast<const T*>(W + frag_block_off<ES>((n0 >> 4) + nt, i * 4 + wave, K));
+    };
+
+    // Epilogue operands do not depend on the product: fetch them first so their latency
+    // overlaps the operand stream.
+    const T* __restrict__ bias = static_cast<const T*>(a.bias);
+    f32x4 e_bias[EP], e_res[EP];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) wrow[nt] = W + (size_t)(n0 + nt * 16 + r) * K + g * 16;
+    for (int j = 0; j < EP; ++j) {
+        const int idx = tid + 256 * j;
+        const int t = idx >> 6, l = idx & 63;
+        const int m = m0 + (t / NT) * 16 + (l & 15);
+        const int n = n0 + (t % NT) * 16 + (l >> 4) * 4;
+        const bool live = idx < MT * NT * 64 && m < M;
+        e_bias[j] = (bias && live) ? load4(bias + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (EPI == EPI_RESID)
+            e_res[j] = live ? *reinterpret_cast<const f32x4*>(static_cast<const char*>(a.out) + frag_elem_off<4>(m, n, a.N))
+                            : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     if constexpr (PRO == PRO_LN) {
-        const float* __restrict__ X = static_cast<const float*>(a.A);
-        float xs[MT][kMaxLnBlocks][16];
-        const float* xrow[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            int m = m0 + mt * 16 + r;
-            m = m < M ? m : M - 1;
-            xrow[mt] = X + (size_t)m * K + g * 16;
-        }
+        const char* __restrict__ X = static_cast<const char*>(a.A);
+        Frag16<float> xs[MT][kMaxLnBlocks];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int i = 0; i < kMaxLnBlocks; ++i)
-                if (i < nblk) load_f32<16>(xrow[mt] + (i * 4 + wave) * 64, xs[mt][i]);
+                if (i < nblk)
+                    xs[mt][i] = load_frag(
+                        reinterpret_cast<const float*>(X + frag_block_off<4>((m0 >> 4) + mt, i * 4 + wave, K)), lane);
+        // the weight stream starts before the statistics are known
+        Frag16<T> wf[NT][kMaxLnBlocks];
+#pragma unroll
+        for (int i = 0; i < kMaxLnBlocks; ++i)
+            if (i < nblk)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) wf[nt][i] = load_frag(wblk(nt, i), lane);
         // row mean
         float mean[MT], rstd[MT];
 #pragma unroll
@@ -105,7 +150,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             for (int i = 0; i < kMaxLnBlocks; ++i)
                 if (i < nblk)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) s += xs[mt][i][e];
+                    for (int e = 0; e < 16; ++e) s += xs[mt][i].v[e];
             s = rows4_sum(s);
             if (g == 0) red[0][wave][mt * 16 + r] = s;
         }
@@ -120,7 +165,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
                 if (b < nblk)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        float c = xs[mt][b][e] - mean[mt];
+                        float c = xs[mt][b].v[e] - mean[mt];
                         s += c * c;
                     }
             s = rows4_sum(s);
@@ -147,39 +192,64 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
                 for (int mt = 0; mt < MT; ++mt) {
                     float y[16];
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) y[e] = (xs[mt][i][e] - mean[mt]) * rstd[mt] * gam[e] + bet[e];
+                    for (int e = 0; e < 16; ++e) y[e] = (xs[mt][i].v[e] - mean[mt]) * rstd[mt] * gam[e] + bet[e];
                     pack_frag(y, af[mt]);
                 }
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    Frag16<T> wf = load_frag(wrow[nt] + k0);
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) mma(acc[mt][nt], wf, af[mt]);
-                }
+                    for (int mt = 0; mt < MT; ++mt) mma(acc[mt][nt], wf[nt][i], af[mt]);
             }
         }
     } else {
-        const T* __restrict__ A = static_cast<const T*>(a.A);
+        const char* __restrict__ A = static_cast<const char*>(a.A);
+        // PRO_RM only: this lane's rows in a row-major source (clamped to the last row)
         const T* arow[MT];
+        if constexpr (PRO == PRO_RM) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            int m = m0 + mt * 16 + r;
-            m = m < M ? m : M - 1;
-            size_t src = a.a_row_map ? (size_t)a.a_row_map[m] : (size_t)m;
-            arow[mt] = A + src * K + g * 16;
+            for (int mt = 0; mt < MT; ++mt) {
+                int m = m0 + mt * 16 + r;
+                m = m < M ? m : M - 1;
+                size_t src = a.a_row_map ? (size_t)a.a_row_map[m] : (size_t)m;
+                arow[mt] = reinterpret_cast<const T*>(A) + src * K + g * 16;
+            }
         }
-#pragma unroll 2
-        for (int i = 0; i < nblk; ++i) {
-            const int k0 = (i * 4 + wave) * 64;
-            Frag16<T> af[MT], wf[NT];
+        // U blocks are fetched per group, two groups in flight (register double buffer)
+        constexpr int U = (MT + NT) <= 2 ? 4 : ((MT + NT) <= 4 ? 2 : 1);
+        Frag16<T> af[2][U][MT], wf[2][U][NT];
+        auto fetch = [&](int buf, int blk0) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wf[nt] = load_frag(wrow[nt] + k0);
+            for (int u = 0; u < U; ++u) {
+                const int i = blk0 + u;
+                if (i < nblk) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[mt] = load_frag(arow[mt] + k0);
+                    for (int nt = 0; nt < NT; ++nt) wf[buf][u][nt] = load_frag(wblk(nt, i), lane);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+                    for (int mt = 0; mt < MT; ++mt) {
+                        if constexpr (PRO == PRO_RM)
+                            af[buf][u][mt] = load_frag_rm(arow[mt] + (i * 4 + wave) * 64);
+                        else
+                            af[buf][u][mt] = load_frag(
+                                reinterpret_cast<const T*>(A + frag_block_off<ES>((m0 >> 4) + mt, i * 4 + wave, K)), lane);
+                    }
+                }
+            }
+        };
+        auto compute = [&](int buf, int blk0) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) mma(acc[mt][nt], wf[nt], af[mt]);
+            for (int u = 0; u < U; ++u)
+                if (blk0 + u < nblk)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) mma(acc[mt][nt], wf[buf][u][nt], af[buf][u][mt]);
+        };
+        fetch(0, 0);
+        for (int b0 = 0; b0 < nblk; b0 += 2 * U) {
+            fetch(1, b0 + U);
+            compute(0, b0);
+            fetch(0, b0 + 2 * U);
+            compute(1, b0 + U);
         }
     }
 
@@ -190,8 +260,10 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         for (int nt = 0; nt < NT; ++nt) part[wave][mt * NT + nt][lane] = acc[mt][nt];
     __syncthreads();
 
-    const T* __restrict__ bias = static_cast<const T*>(a.bias);
-    for (int idx = tid; idx < MT * NT * 64; idx += 256) {
+#pragma unroll
+    for (int j = 0; j < EP; ++j) {
+        const int idx = tid + 256 * j;
+        if (idx >= MT * NT * 64) continue;
         const int t = idx >> 6, l = idx & 63;
         f32x4 s = part[0][t][l];
         s += part[1][t][l];
@@ -201,17 +273,14 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         const int m = m0 + mt * 16 + (l & 15);
         const int n = n0 + nt * 16 + (l >> 4) * 4;
         if (m >= M) continue;
-        if (bias) s += load4(bias + n);
+        s += e_bias[j];
         if constexpr (EPI == EPI_RESID) {
-            float* p = static_cast<float*>(a.out) + (size_t)m * a.N + n;
-            f32x4 v = *reinterpret_cast<f32x4*>(p);
-            v += s;
-            *reinterpret_cast<f32x4*>(p) = v;
+            *reinterpret_cast<f32x4*>(static_cast<char*>(a.out) + frag_elem_off<4>(m, n, a.N)) = e_res[j] + s;
         } else if constexpr (EPI == EPI_F32) {
             store4(static_cast<float*>(a.out) + (size_t)m * a.N + n, s);
         } else if constexpr (EPI == EPI_RELU_T) {
             s[0] = fmaxf(s[0], 0.f); s[1] = fmaxf(s[1], 0.f); s[2] = fmaxf(s[2], 0.f); s[3] = fmaxf(s[3], 0.f);
-            store4(static_cast<T*>(a.out) + (size_t)m * a.N + n, s);
+            store4(reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<ES>(m, n, a.N)), s);
         } else if constexpr (EPI == EPI_QKV) {
             const int d = a.d_model;
             if (n < d) {
@@ -243,13 +312,33 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Tile choice by a traffic model: a launch runs ceil(workgroups / 256) rounds on
+// the 256 CUs and each workgroup pulls (BM * bytes(A) + BN * bytes(W)) * K
+// through its CU; pick the candidate with the least bytes per CU, then the
+// fewest workgroups.
 template <typename T, int PRO, int EPI>
 static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
-    // Tile choice: enough workgroups to cover the 256 CUs while keeping the
-    // per-workgroup operand traffic (BM + BN) * K small.
-    if (a.M <= 128) return launch_one<T, PRO, EPI, 1, 1>(a, s);
-    if (a.M <= 512) return launch_one<T, PRO, EPI, 2, 2>(a, s);
-    return launch_one<T, PRO, EPI, 2, 4>(a, s);
+    struct Cand { int mt, nt; };
+    static const Cand cands[] = {{1, 1}, {2, 2}, {2, 4}, {4, 2}, {4, 4}};
+    const double a_bytes = PRO == PRO_LN ? 4.0 : sizeof(T), w_bytes = sizeof(T);
+    int best = 0;
+    double best_cost = 1e300;
+    long best_wgs = 0;
+    const int n_cands = sizeof(T) == 4 ? 2 : 5;  // float32 fragments are twice as wide: small tiles only
+    for (int c = 0; c < n_cands; ++c) {
+        const int bm = 16 * cands[c].mt, bn = 16 * cands[c].nt;
+        if (a.N % bn != 0) continue;
+        const long wgs = (long)((a.M + bm - 1) / bm) * (a.N / bn);
+        const double cost = (double)((wgs + 255) / 256) * (bm * a_bytes + bn * w_bytes);
+        if (cost < best_cost || (cost == best_cost && wgs < best_wgs)) { best = c; best_cost = cost; best_wgs = wgs; }
+    }
+    switch (best) {
+        case 0: return launch_one<T, PRO, EPI, 1, 1>(a, s);
+        case 1: return launch_one<T, PRO, EPI, 2, 2>(a, s);
+        case 2: return launch_one<T, PRO, EPI, 2, 4>(a, s);
+        case 3: return launch_one<T, PRO, EPI, 4, 2>(a, s);
+        default: return launch_one<T, PRO, EPI, 4, 4>(a, s);
+    }
 }
 
 template <typename T>
@@ -258,7 +347,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a, hipS
     if (pro == PRO_LN && epi == EPI_F32) return launch_tiles<T, PRO_LN, EPI_F32>(a, s);
     if (pro == PRO_LN && epi == EPI_RELU_T) return launch_tiles<T, PRO_LN, EPI_RELU_T>(a, s);
     if (pro == PRO_T && epi == EPI_RESID) return launch_tiles<T, PRO_T, EPI_RESID>(a, s);
-    if (pro == PRO_T && epi == EPI_CROSSKV) return launch_tiles<T, PRO_T, EPI_CROSSKV>(a, s);
+    if (pro == PRO_RM && epi == EPI_CROSSKV) return launch_tiles<T, PRO_RM, EPI_CROSSKV>(a, s);
     return hipErrorInvalidValue;
 }
 
@@ -266,6 +355,34 @@ hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hi
     if (a.M < 1 || a.K % 256 != 0 || a.N % 64 != 0) return hipErrorInvalidValue;
     if (pro == PRO_LN && a.K > 256 * kMaxLnBlocks) return hipErrorInvalidValue;
     return dt == kBF16 ? launch_typed<bf16_t>(pro, epi, a, s) : launch_typed<float>(pro, epi, a, s);
+}
+
+// ---------------------------------------------------------------- weight re-ordering
+// dst (fragment order) <- src (row-major [N, K]); one thread per 16-byte piece.
+template <typename T>
+__global__ __launch_bounds__(256) void reorder_weight_kernel(const T* __restrict__ src, char* __restrict__ dst, int N,
+                                                             int K) {
+    constexpr int ES = sizeof(T), EPP = 16 / ES;
+    const size_t piece = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t n_pieces = (size_t)N * K / EPP;
+    if (piece >= n_pieces) return;
+    const int n = (int)(piece / (K / EPP));
+    const int k = (int)(piece % (K / EPP)) * EPP;
+    const f32x4 v = *reinterpret_cast<const f32x4*>(src + (size_t)n * K + k);  // 16 bytes, any type
+    *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(n, k, K)) = v;
+}
+
+hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s) {
+    if (N % 16 != 0 || K % 64 != 0) return hipErrorInvalidValue;
+    const size_t pieces = (size_t)N * K / (dt == kBF16 ? 8 : 4);
+    dim3 grid((unsigned)((pieces + 255) / 256));
+    if (dt == kBF16)
+        hipLaunchKernelGGL(reorder_weight_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(src),
+                           static_cast<char*>(dst), N, K);
+    else
+        hipLaunchKernelGGL(reorder_weight_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(src),
+                           static_cast<char*>(dst), N, K);
+    return hipGetLastError();
 }
 
 }  // namespace aed

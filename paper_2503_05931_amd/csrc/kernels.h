@@ -11,20 +11,21 @@ constexpr int kPage = 16;  // tokens per self-attention KV page
 
 // ---------------------------------------------------------------- decode GEMM
 // C[M,N] = prologue(A)[M,K] . W[N,K]^T (+bias), then an epilogue.
-enum GemmPro { PRO_LN = 0, PRO_T = 1 };
+enum GemmPro { PRO_LN = 0, PRO_T = 1, PRO_RM = 2 };
 enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROSSKV = 4 };
 
 struct GemmArgs {
-    const void* A;        // PRO_LN: float [M,K] (residual stream); PRO_T: T [rows,K]
-    const int* a_row_map; // PRO_T only, may be null: A row of output row m is a_row_map[m]
-    const void* W;        // T [N,K]
+    const void* A;        // PRO_LN: float [M,K] (residual stream), fragment order; PRO_T: T [M,K], fragment
+                          // order; PRO_RM: T [rows,K] row-major
+    const int* a_row_map; // PRO_RM only, may be null: A row of output row m is a_row_map[m]
+    const void* W;        // T [N,K] in fragment order (launch_reorder_weight)
     const void* bias;     // T [N] or null
     const void* ln_g;     // T [K]  (PRO_LN)
     const void* ln_b;     // T [K]
     float ln_eps;
     int M, N, K;
-    void* out;            // EPI_RESID: float [M,N], += ; EPI_F32: float [M,N]; EPI_RELU_T: T [M,N];
-                          // EPI_QKV: float q [M,d_model]
+    void* out;            // EPI_RESID: float [M,N] fragment order, += ; EPI_F32: float [M,N] row-major;
+                          // EPI_RELU_T: T [M,N] fragment order; EPI_QKV: float q [M,d_model] row-major
     // EPI_QKV: columns [d,2d) and [2d,3d) go to the paged self-attention cache of this layer
     void* k_pool;         // T [pages][H][16][Dh]
     void* v_pool;
@@ -39,14 +40,17 @@ struct GemmArgs {
     long long t_cap;
 };
 
+// Buffers in fragment order must hold a multiple of 64 rows (rows >= M are read, never written).
 // Returns hipSuccess or the launch error.  Requirements (checked by the caller):
 // K % 256 == 0, N % 64 == 0, PRO_LN: K <= 1024.
 hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s);
+// dst (fragment order) <- src (row-major [N,K]); N % 16 == 0, K % 64 == 0
+hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s);
 
 // ---------------------------------------------------------------- decode attention
 struct AttnArgs {
     const float* q;       // [B, d_model]
-    void* out;            // T [B, d_model]
+    void* out;            // T [B, d_model] in fragment order
     const void* K;        // self: T [pages][H][16][Dh]; cross: T [H][t_cap][Dh]  (this layer)
     const void* V;
     const int* finished;  // [B]
@@ -54,7 +58,7 @@ struct AttnArgs {
     const int* page_table;
     int max_pages;
     const int* seq_len;   // keys = seq_len[b] + 1
-    int chunk;            // keys per work item, multiple of 64
+    int chunk;            // keys per work item, multiple of 64 (self and cross)
     int n_chunks_max;     // grid.z
     int batch;
     // cross
@@ -64,7 +68,6 @@ struct AttnArgs {
     long long t_cap;
     // split-K merge
     float* part;          // [B*H][max_chunks][Dh+2]
-    int* counters;        // [B*H], zero between launches
     int max_chunks;
     int n_heads, head_dim;
     float scale_log2e;    // log2(e) / sqrt(Dh)
@@ -80,7 +83,7 @@ struct StateArgs {
     int prompt_len, prompt_stride, out_stride, max_new;
     int eos_id, pad_id, batch, vocab;
 };
-// x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]
+// x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]   (x in fragment order)
 hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,
                         int d_model, int max_positions, float emb_scale, hipStream_t s);
 // greedy = 1: prompt feeding, argmax, EOS rules, output writes; greedy = 0: argmax only -> step_out (may be null)

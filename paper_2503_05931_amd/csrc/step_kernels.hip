@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void embed_kernel(float* __restrict__ x, const
         o[1] = emb_scale * ev[1] + pv[1];
         o[2] = emb_scale * ev[2] + pv[2];
         o[3] = emb_scale * ev[3] + pv[3];
-        store4(x + (size_t)b * d + i, o);
+        store4(reinterpret_cast<float*>(reinterpret_cast<char*>(x) + frag_elem_off<4>(b, i, d)), o);
     }
 }
 
