@@ -25,7 +25,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 
-def run_workload(name, steps, warmup, want_roofline):
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None when there is none for
+    this kernel and workload or the kernel's source has changed since the counters were taken."""
+    import hashlib
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get(kernel)
+        if not rec or rec["workload"] != workload:
+            return None
+        h = hashlib.sha256(open(os.path.join(ROOT, rec["source"]), "rb").read()).hexdigest()[:16]
+        return rec["traffic_bytes_per_launch"] if h == rec["sha256_16"] else None
+    except (OSError, ValueError, KeyError):
+        return None
+
+
+def run_workload(name, steps, warmup, want_roofline, eager=False):
     import numpy as np
     import torch
     from paper_2503_05931_amd import binding, workloads as W
@@ -33,8 +47,11 @@ def run_workload(name, steps, warmup, want_roofline):
     wl = W.make(name)
     cfg = wl.cfg
     B = cfg.batch
+    # eager: the library is given the default (NULL) stream, on which it launches every kernel directly
+    # instead of replaying a captured graph (used for hardware-counter runs)
     dec = binding.Decoder(cfg, wl.weights, max_batch=B, max_total_enc_frames=int(wl.enc_lens.sum()),
-                          max_dec_len=cfg.max_dec_len)
+                          max_dec_len=cfg.max_dec_len,
+                          stream=torch.cuda.default_stream(torch.device("cuda:0")) if eager else None)
     enc = dec.to_device(wl.enc)
     prompt = torch.from_numpy(wl.prompt).to(dec.device)
     out_tokens = torch.empty((B, cfg.max_new), dtype=torch.int32, device=dec.device)
@@ -95,7 +112,7 @@ def run_workload(name, steps, warmup, want_roofline):
         p = per[dom]
         res["kernels"] = {k: {"us": round(v["us"], 2), "GBps": round(v["GBps"], 1)} for k, v in per.items()}
         res["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": p["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": p["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                           "frac": p["GBps"] / HBM_PEAK_GBS, "traffic": measured_traffic(dom, name),
                            "avg_launch_us": p["us"], "algorithmic_bytes_per_launch": p["bytes"]}
     dec.close()
     return res, wl
@@ -123,6 +140,11 @@ def main():
     ap.add_argument("--workload", default="canary24_b64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="skip the 4-layer decoder's extra line")
+    ap.add_argument("--eager", action="store_true",
+                    help="launch kernels directly on the default stream instead of replaying the captured graph")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known size to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters with)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the decoder shards by sequence with no exchange between GPUs, "
@@ -133,7 +155,14 @@ def main():
         print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
         sys.exit(1)
 
-    res, wl = run_workload(args.workload, args.steps, args.warmup, want_roofline=True)
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)   # one copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+    res, wl = run_workload(args.workload, args.steps, args.warmup, want_roofline=True, eager=args.eager)
     cfg = wl.cfg
     line = {
         "metric": "decoded tokens/sec at 1 MI355X (24L and 4L decoder) + % HBM/MFMA roofline",
@@ -151,7 +180,8 @@ def main():
         "config": {"workload": args.workload, "n_layers": cfg.n_layers, "d_model": cfg.d_model,
                    "batch": cfg.batch, "prompt_len": cfg.prompt_len, "max_new": cfg.max_new,
                    "enc_frames_total": int(wl.enc_lens.sum()),
-                   "step": "cross K/V precompute + greedy decode of the batch"},
+                   "step": "cross K/V precompute + greedy decode of the batch",
+                   "launch": "eager" if args.eager else "graph"},
         "decode_only_tokens_per_s": res["decode_only_tokens_per_s"],
         "decode_ms_per_token_step": res["decode_ms_per_token_step"],
         "precompute_ms": res["precompute_ms"],

@@ -19,7 +19,7 @@ using namespace aed;
 namespace {
 
 constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
-constexpr int kTargetItems = 512;   // work items aimed at per attention launch when sequences are cut
+constexpr int kTargetItems = 512;      // work items aimed at per attention launch when sequences are cut
 constexpr int kMinItemsNoSplit = 128;  // batch * heads from which sequences are never cut
 
 thread_local std::string g_create_error;
@@ -183,10 +183,13 @@ aed_status fail(aed_decoder* d, aed_status st, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail(d, AED_EHIP, "%s: %s", #expr, hipGetErrorString(e_));  \
     } while (0)
 
-// Keys per attention work item.  One workgroup per (sequence, head) streams at
-// most a few hundred keys, so sequences are cut into chunks only when
-// batch * heads leaves most of the 256 CUs idle; then the chunk aims at
-// kTargetItems items, at least 64 keys each, at most kMaxChunks per sequence.
+// Keys per attention work item.  Whole sequences (one workgroup per sequence and
+// head, no merge pass) whenever batch * heads gives the 256 CUs something to do;
+// measured on MI355X, cutting the 24-layer batch-64 workload into 128-key chunks
+// made the attention kernel no faster and added a 4 us merge launch.  Only a
+// batch too small to occupy the GPU (batch * heads < kMinItemsNoSplit) has its
+// long sequences cut, aiming at kTargetItems items of at least 64 keys and at
+// most kMaxChunks per sequence.
 int pick_chunk(long long total_keys, int max_len, int batch, int n_heads) {
     const long long whole = std::max<long long>(64, ((long long)max_len + 63) / 64 * 64);
     if ((long long)batch * n_heads >= kMinItemsNoSplit) return (int)whole;
@@ -273,7 +276,7 @@ hipError_t k_cross_attn(aed_decoder* d, int l) {
     AttnArgs a = attn_base(d);
     a.K = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     a.V = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
-    a.items = d->at<int4>(d->lay.items);
+    a.items = d->n_items > d->batch ? d->at<int4>(d->lay.items) : nullptr;  // list only when some sequence is cut
     a.n_items = d->n_items;
     a.enc_off = d->at<int>(d->lay.enc_off);
     a.chunk = d->cross_chunk;
@@ -365,6 +368,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     int max_len = 0;
     for (int b = 0; b < batch; ++b) {
         if (enc_lens[b] < 1) return fail(d, AED_EINVAL, "enc_lens[%d] = %d (must be >= 1)", b, enc_lens[b]);
+        if (enc_lens[b] > 65535) return fail(d, AED_EUNSUPPORTED, "enc_lens[%d] = %d: more than 65535 frames per sequence", b, enc_lens[b]);
         if (padded && enc_lens[b] > t_max) return fail(d, AED_EINVAL, "enc_lens[%d] = %d > t_max %d", b, enc_lens[b], t_max);
         total += enc_lens[b];
         max_len = std::max(max_len, enc_lens[b]);
@@ -381,7 +385,8 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
         const int nc = (enc_lens[b] + chunk - 1) / chunk;
         for (int c = 0; c < nc; ++c) {
             int4 it;
-            it.x = b; it.y = c * chunk; it.z = std::min(chunk, enc_lens[b] - c * chunk); it.w = c | (nc << 16);
+            it.x = b; it.y = (c * chunk) | (c << 16); it.z = std::min(chunk, enc_lens[b] - c * chunk) | (nc << 16);
+            it.w = off[b];
             items.push_back(it);
         }
     }

@@ -9,8 +9,10 @@
 // once.  Cross-attention: items come from a list built on the host from the
 // true encoder lengths, so neither padding frames nor empty chunks exist.
 //
-// Inside a workgroup (4 wavefronts) the chunk is cut into 16-key blocks
-// (= one page of the self-attention cache), wavefront w takes blocks w, w+4,..
+// Inside a workgroup (NW = 4 or 8 wavefronts) the chunk is cut into 16-key blocks
+// (= one page of the self-attention cache), wavefront w takes blocks w, w+NW,..
+// and keeps two blocks in flight (the next block is fetched while the current
+// one is consumed).
 // A wavefront reads a block as 4 keys per load instruction: lane (r, g) loads
 // 16 bytes (or 8) -- the slice r of head_dim -- of key 4 i + g, i = 0..3, so
 // each instruction covers 4 whole rows (1 KB for bf16 head_dim 128).  The dot
@@ -28,40 +30,90 @@
 
 namespace aed {
 
-template <typename T, int N> __device__ __forceinline__ void load_row(const T* p, float* out) {
-    load_f32<N>(p, out);
-}
+// One key row slice as it sits in memory (EPL elements of T), kept raw in
+// registers until it is used so that two blocks can be in flight per wavefront.
+template <typename T, int EPL> struct RawRow;
+template <> struct RawRow<bf16_t, 8> { bf16x8 v; };
+template <> struct RawRow<bf16_t, 4> { bf16x4 v; };
+template <> struct RawRow<float, 8> { f32x4 v[2]; };
+template <> struct RawRow<float, 4> { f32x4 v[1]; };
 
-template <typename T, int DH, bool SELF>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
+template <int EPL> __device__ __forceinline__ RawRow<bf16_t, EPL> load_raw(const bf16_t* p) {
+    RawRow<bf16_t, EPL> r;
+    r.v = *reinterpret_cast<const decltype(r.v)*>(p);
+    return r;
+}
+template <int EPL> __device__ __forceinline__ RawRow<float, EPL> load_raw(const float* p) {
+    RawRow<float, EPL> r;
+#pragma unroll
+    for (int i = 0; i < EPL / 4; ++i) r.v[i] = reinterpret_cast<const f32x4*>(p)[i];
+    return r;
+}
+template <int EPL> __device__ __forceinline__ float raw_at(const RawRow<bf16_t, EPL>& r, int e) { return (float)r.v[e]; }
+template <int EPL> __device__ __forceinline__ float raw_at(const RawRow<float, EPL>& r, int e) { return r.v[e >> 2][e & 3]; }
+
+template <typename T, int DH, bool SELF, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     constexpr int EPL = DH / 16;  // head_dim elements per lane
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const int h = blockIdx.x, H = a.n_heads;
 
-    int b, start, n, chunk_idx, n_chunks;
+    // Work item: with a work list (cross-attention cut into chunks) the item names its sequence and
+    // key range; otherwise blockIdx.y is the sequence, so that the per-sequence scalars below are
+    // all fetched in one round trip.
+    int b, start, n, chunk_idx, n_chunks, row0 = 0;
     if constexpr (SELF) {
         b = blockIdx.y;
-        if (a.finished[b]) return;
+        const int fin = a.finished[b];
         const int total = a.seq_len[b] + 1;
+        if (fin) return;
         n_chunks = (total + a.chunk - 1) / a.chunk;
         chunk_idx = blockIdx.z;
         if (chunk_idx >= n_chunks) return;
         start = chunk_idx * a.chunk;
         n = min(a.chunk, total - start);
-    } else {
+    } else if (a.items) {
         const int4 it = a.items[blockIdx.y];
         b = it.x;
+        start = it.y & 0xFFFF;
+        chunk_idx = it.y >> 16;
+        n = it.z & 0xFFFF;
+        n_chunks = it.z >> 16;
+        row0 = it.w + start;  // first frame of this chunk in the packed layout
         if (a.finished[b]) return;
-        start = it.y;
-        n = it.z;
-        chunk_idx = it.w & 0xFFFF;
-        n_chunks = it.w >> 16;
+    } else {
+        b = blockIdx.y;
+        const int fin = a.finished[b];
+        const int o0 = a.enc_off[b], o1 = a.enc_off[b + 1];
+        if (fin) return;
+        start = 0; chunk_idx = 0; n_chunks = 1;
+        n = o1 - o0;
+        row0 = o0;
     }
 
     const T* __restrict__ Kb = static_cast<const T*>(a.K);
     const T* __restrict__ Vb = static_cast<const T*>(a.V);
     size_t cross_base = 0;
-    if constexpr (!SELF) cross_base = ((size_t)h * a.t_cap + a.enc_off[b] + start) * DH;
+    if constexpr (!SELF) cross_base = ((size_t)h * a.t_cap + row0) * DH;
+    const int n_blocks = (n + 15) >> 4;
+    const int* __restrict__ pages = SELF ? a.page_table + (size_t)b * a.max_pages + (start >> 4) : nullptr;
+
+    typedef RawRow<T, EPL> Raw;
+    // element offset of this lane's slice of key (4 i + g) of block kb (clamped to the valid keys)
+    auto fetch = [&](int kb, Raw* kf, Raw* vf) {
+        size_t blk_base;
+        if constexpr (SELF) blk_base = ((size_t)pages[kb] * H + h) * kPage * DH;
+        else blk_base = cross_base + (size_t)kb * 16 * DH;
+        const int last = n - 1 - kb * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = i * 4 + g;
+            const int jc = j < last ? j : last;  // never read past the valid keys
+            const size_t off = blk_base + (size_t)jc * DH + r * EPL;
+            kf[i] = load_raw<EPL>(Kb + off);
+            vf[i] = load_raw<EPL>(Vb + off);
+        }
+    };
 
     float q[EPL];
     {
@@ -76,30 +128,15 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    for (int kb = wave; kb * 16 < n; kb += 4) {
-        size_t blk_base;
-        if constexpr (SELF) {
-            const int page = a.page_table[(size_t)b * a.max_pages + (start >> 4) + kb];
-            blk_base = ((size_t)page * H + h) * kPage * DH;
-        } else {
-            blk_base = cross_base + (size_t)kb * 16 * DH;
-        }
-        const int last = n - 1 - kb * 16;  // last valid key of this block (>= 0)
-        float kf[4][EPL], vf[4][EPL];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = i * 4 + g;
-            const int jc = j < last ? j : last;  // clamp: never read past the valid keys
-            load_row<T, EPL>(Kb + blk_base + (size_t)jc * DH + r * EPL, kf[i]);
-            load_row<T, EPL>(Vb + blk_base + (size_t)jc * DH + r * EPL, vf[i]);
-        }
+    auto consume = [&](int kb, const Raw* kf, const Raw* vf) {
+        const int last = n - 1 - kb * 16;
         float s[4];
         float m_blk = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             float d = 0.f;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) d = fmaf(q[e], kf[i][e], d);
+            for (int e = 0; e < EPL; ++e) d = fmaf(q[e], raw_at<EPL>(kf[i], e), d);
             d = row16_sum(d);
             s[i] = (i * 4 + g <= last) ? d : -INFINITY;
             m_blk = fmaxf(m_blk, s[i]);
@@ -115,43 +152,58 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
             const float p = __builtin_amdgcn_exp2f(s[i] - m_new);
             l_run += p;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[i][e], acc[e]);
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, raw_at<EPL>(vf[i], e), acc[e]);
         }
         m_run = m_new;
+    };
+
+    // two blocks in flight per wavefront: fetch block i+1 while block i is consumed
+    Raw k0[4], v0[4], k1[4], v1[4];
+    int kb = wave;
+    if (kb < n_blocks) fetch(kb, k0, v0);
+    while (kb < n_blocks) {
+        if (kb + NW < n_blocks) fetch(kb + NW, k1, v1);
+        consume(kb, k0, v0);
+        kb += NW;
+        if (kb >= n_blocks) break;
+        if (kb + NW < n_blocks) fetch(kb + NW, k0, v0);
+        consume(kb, k1, v1);
+        kb += NW;
     }
     // lanes of different rows g hold different keys: add them up
     l_run = rows4_sum(l_run);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = rows4_sum(acc[e]);
 
-    __shared__ float sm_acc[4][DH];
-    __shared__ float sm_m[4], sm_l[4];
+    __shared__ float sm_acc[NW][DH];
+    __shared__ float sm_m[NW], sm_l[NW];
     if (g == 0) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) sm_acc[wave][r * EPL + e] = acc[e];
     }
     if (lane == 0) { sm_m[wave] = m_run; sm_l[wave] = l_run; }
     __syncthreads();
+    if (tid >= DH) return;
 
-    // merge the four wavefronts (a wavefront without keys has m = -inf, l = 0, acc = 0)
-    float m_tot = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+    // merge the wavefronts in order (a wavefront without keys has m = -inf, l = 0, acc = 0)
+    float m_tot = sm_m[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) m_tot = fmaxf(m_tot, sm_m[w]);
     float l_tot = 0.f, o = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
         const float f = __builtin_amdgcn_exp2f(sm_m[w] - m_tot);
         l_tot += sm_l[w] * f;
-        if (tid < DH) o += sm_acc[w][tid] * f;
+        o += sm_acc[w][tid] * f;
     }
     if (n_chunks == 1) {  // the output feeds the next GEMM: fragment order
-        if (tid < DH)
-            *reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + tid, H * DH)) =
-                from_f32<T>(o / l_tot);
+        *reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + tid, H * DH)) =
+            from_f32<T>(o / l_tot);
         return;
     }
-
     // ---- several chunks: publish the partial; attn_merge_kernel combines them in chunk order ----
     float* __restrict__ my = a.part + ((size_t)(b * H + h) * a.max_chunks + chunk_idx) * (DH + 2);
-    if (tid < DH) my[tid] = o;
+    my[tid] = o;
     if (tid == 0) { my[DH] = m_tot; my[DH + 1] = l_tot; }
 }
 
@@ -181,14 +233,19 @@ __global__ __launch_bounds__(DH) void attn_merge_kernel(AttnArgs a) {
         from_f32<T>(O / L);
 }
 
+// Wavefronts per workgroup: 8 when the launch has few workgroups (the longest
+// sequence sets the kernel's duration), 4 when there are plenty.
 template <typename T, bool SELF>
 static hipError_t launch_dh(const AttnArgs& a, dim3 grid, bool merge, hipStream_t s) {
     dim3 mgrid(a.n_heads, a.batch);
+    const bool wide = (size_t)grid.x * grid.y * grid.z <= 2048;
     if (a.head_dim == 128) {
-        hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF>), grid, dim3(256), 0, s, a);
+        if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF, 8>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF, 4>), grid, dim3(256), 0, s, a);
         if (merge) hipLaunchKernelGGL((attn_merge_kernel<T, 128, SELF>), mgrid, dim3(128), 0, s, a);
     } else if (a.head_dim == 64) {
-        hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF>), grid, dim3(256), 0, s, a);
+        if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF, 8>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF, 4>), grid, dim3(256), 0, s, a);
         if (merge) hipLaunchKernelGGL((attn_merge_kernel<T, 64, SELF>), mgrid, dim3(64), 0, s, a);
     } else {
         return hipErrorInvalidValue;
@@ -205,9 +262,9 @@ hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s) {
-    if (a.n_items < 1 || a.chunk < 64 || a.chunk % 64 != 0) return hipErrorInvalidValue;
-    dim3 grid(a.n_heads, a.n_items);
-    const bool merge = a.n_items > a.batch;
+    if (a.chunk < 64 || a.chunk % 64 != 0 || (a.items && a.n_items < a.batch)) return hipErrorInvalidValue;
+    dim3 grid(a.n_heads, a.items ? a.n_items : a.batch);
+    const bool merge = a.items != nullptr;
     return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, merge, s) : launch_dh<float, false>(a, grid, merge, s);
 }
 

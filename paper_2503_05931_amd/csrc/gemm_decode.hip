@@ -70,6 +70,14 @@ __device__ __forceinline__ void pack_frag(const float* y, Frag16<float>& f) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) f.v[i] = y[i];
 }
+__device__ __forceinline__ void unpack_frag(const Frag16<bf16_t>& f, float* y) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { y[i] = (float)f.lo[i]; y[8 + i] = (float)f.hi[i]; }
+}
+__device__ __forceinline__ void unpack_frag(const Frag16<float>& f, float* y) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) y[i] = f.v[i];
+}
 // acc[n-major 16x16] += W-fragment x A-fragment over the 64-wide k block
 __device__ __forceinline__ void mma(f32x4& acc, const Frag16<bf16_t>& w, const Frag16<bf16_t>& a) {
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.lo, a.lo, acc, 0, 0, 0);
@@ -141,6 +149,16 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             if (i < nblk)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) wf[nt][i] = load_frag(wblk(nt, i), lane);
+        // LayerNorm gain/shift for this lane's k values, fetched before the statistics are known
+        const T* __restrict__ G = static_cast<const T*>(a.ln_g);
+        const T* __restrict__ Bt = static_cast<const T*>(a.ln_b);
+        Frag16<T> gam_f[kMaxLnBlocks], bet_f[kMaxLnBlocks];
+#pragma unroll
+        for (int i = 0; i < kMaxLnBlocks; ++i)
+            if (i < nblk) {
+                gam_f[i] = load_frag_rm(G + (i * 4 + wave) * 64 + g * 16);
+                bet_f[i] = load_frag_rm(Bt + (i * 4 + wave) * 64 + g * 16);
+            }
         // row mean
         float mean[MT], rstd[MT];
 #pragma unroll
@@ -178,15 +196,12 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             float var = (red[1][0][i] + red[1][1][i] + red[1][2][i] + red[1][3][i]) / (float)K;
             rstd[mt] = 1.0f / sqrtf(var + a.ln_eps);
         }
-        const T* __restrict__ G = static_cast<const T*>(a.ln_g);
-        const T* __restrict__ Bt = static_cast<const T*>(a.ln_b);
 #pragma unroll
         for (int i = 0; i < kMaxLnBlocks; ++i) {
             if (i < nblk) {
-                const int k0 = (i * 4 + wave) * 64;
                 float gam[16], bet[16];
-                load_f32<16>(G + k0 + g * 16, gam);
-                load_f32<16>(Bt + k0 + g * 16, bet);
+                unpack_frag(gam_f[i], gam);
+                unpack_frag(bet_f[i], bet);
                 Frag16<T> af[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
