@@ -45,3 +45,87 @@ def test_canary24_b64_sampled_sequences(oracle):
     others = [b for b in range(len(wl.enc_lens)) if b not in SAMPLE]
     assert (gids[others][:, P - 1:] == toks[others]).all()
     dec.close()
+
+
+def _forced_check(oracle, wl, sample, n_new, tol, max_dec_len=None):
+    """Greedy-decode the oracle on the sampled sequences for n_new tokens, then run the whole batch through
+    the HIP step path teacher-forced (sampled rows on the oracle's tokens, the rest on token 5) and compare."""
+    import torch
+    from tests import gpu_util as G
+    cfg = wl.cfg
+    sub = wl.subset(sample)
+    m = oracle.Model(cfg, wl.weights)
+    ref_toks, ref_lens, ref_logits = m.greedy_decode(sub.enc, sub.enc_lens, sub.prompt, n_new, want_logits=True)
+    B, P = len(wl.enc_lens), cfg.prompt_len
+    forced = np.full((B, P + n_new - 1), 5, np.int32)
+    forced[:, :P] = wl.prompt
+    for i, b in enumerate(sample):
+        forced[b, P:] = ref_toks[i, :-1]
+    dec = G.make_decoder(wl, max_dec_len=max_dec_len, poison=True)
+    glog, gids = G.forced_logits_gpu(dec, wl, forced)
+    err, near = G.check_forced(ref_logits, glog[sample][:, P - 1:], gids[sample][:, P - 1:], tol)
+    return dec, err, near
+
+
+def test_flash4_b256_sampled_sequences(oracle):
+    """4-layer decoder, batch 256 (the shallow-decoder configuration)."""
+    from tests import gpu_util as G
+    import torch
+    wl = W.make("flash4_b256")
+    sample = [0, 100, 201, 255]
+    dec, err, near = _forced_check(oracle, wl, sample, 40, G.TOL["bf16"])
+    print(f"flash4_b256 teacher-forced: max |dlogit| = {err:.3e}, near ties {near}")
+    # the graph path at full length: every sequence emits exactly max_new tokens, run twice bit-identical
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    prompt = torch.from_numpy(wl.prompt).to(dec.device)
+    t1, l1 = dec.aed_greedy_decode(prompt, wl.cfg.max_new)
+    t1, l1 = t1.cpu().numpy().copy(), l1.cpu().numpy().copy()
+    t2, l2 = dec.aed_greedy_decode(prompt, wl.cfg.max_new)
+    assert (l1 == wl.cfg.max_new).all() and (t1 == t2.cpu().numpy()).all() and (l1 == l2.cpu().numpy()).all()
+    dec.close()
+
+
+def test_ragged24_b128_forced_eos(oracle):
+    """Ragged stress: 128 sequences with mixed encoder lengths and per-sequence forced EOS."""
+    from tests import gpu_util as G
+    import torch
+    wl = W.make("ragged24_b128")
+    cfg = wl.cfg
+    target = wl.max_new_per_seq
+    order = np.argsort(target)
+    sample = [int(order[0]), int(order[3]), int(order[10])]          # short targets keep the oracle cheap
+    sub = wl.subset(sample)
+    m = oracle.Model(cfg, wl.weights)
+    ref_t, ref_l, ref_logits = m.greedy_decode(sub.enc, sub.enc_lens, sub.prompt, cfg.max_new,
+                                               max_new_per_seq=target[sample], want_logits=True)
+    dec = G.make_decoder(wl, poison=True)
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    toks, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), cfg.max_new, max_new_per_seq=target)
+    toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+    # properties that hold for every sequence
+    assert (lens >= 1).all() and (lens <= target).all()
+    for b in range(len(target)):
+        assert toks[b, lens[b] - 1] == cfg.eos_id                       # ends with EOS (forced or natural)
+        assert (toks[b, :lens[b] - 1] != cfg.eos_id).all()
+        assert (toks[b, lens[b]:] == cfg.pad_id).all()
+    # sampled sequences against the oracle, up to the first near tie
+    tol = G.TOL["bf16"]
+    for i, b in enumerate(sample):
+        n = ref_l[i]
+        first = G.first_near_tie(ref_logits[i:i + 1, :n], tol)[0]
+        assert (toks[b, :first] == ref_t[i, :first]).all()
+        if first >= n:
+            assert lens[b] == n and (toks[b] == ref_t[i]).all()
+    print("ragged24_b128: lens ok for 128 sequences; sampled targets", target[sample].tolist(), "oracle lens", ref_l.tolist())
+    dec.close()
+
+
+def test_large24_b1024_paged_sampled_sequences(oracle):
+    """Large batch: 1024 sequences of 500 frames, capacity for 452 positions in 16-token pages
+    (about 100 GB of workspace); a short teacher-forced run crossing one page boundary."""
+    from tests import gpu_util as G
+    wl = W.make("large24_b1024")
+    sample = [0, 1023]
+    dec, err, near = _forced_check(oracle, wl, sample, 16, G.TOL["bf16"], max_dec_len=wl.cfg.max_dec_len)
+    print(f"large24_b1024 teacher-forced: max |dlogit| = {err:.3e}, near ties {near}")
+    dec.close()
