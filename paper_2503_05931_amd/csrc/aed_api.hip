@@ -28,10 +28,10 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Offsets (bytes) of everything carved from the caller's workspace.
 struct Layout {
-    size_t x, q, logits, attn_out, ffn_h;
+    size_t x, q, logits, attn_out, ffn_h, ln_h;
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished;
-    size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part;
-    size_t k_pool, v_pool, kc, vc, w_frag;
+    size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part, counters;
+    size_t k_pool, v_pool, kc, vc, w_frag, enc_frag;
     size_t total;
     int max_pages, n_pages, max_items;
     size_t pool_layer_elems, cross_layer_elems;
@@ -78,6 +78,7 @@ void make_layout(const aed_config* c, Layout* L) {
     L->logits = take(B * (size_t)c->vocab * 4);
     L->attn_out = take(Bp * d * e);
     L->ffn_h = take(Bp * (size_t)c->d_ffn * e);
+    L->ln_h = take(Bp * d * e);
     L->seq_len = take(B * 4);
     L->n_gen = take(B * 4);
     L->finished = take(B * 4);
@@ -92,19 +93,23 @@ void make_layout(const aed_config* c, Layout* L) {
     L->row_map = take((size_t)c->max_total_enc_frames * 4);
     L->items = take((size_t)L->max_items * 16);
     L->part = take(B * H * kMaxChunks * (Dh + 2) * 4);
+    L->counters = take(B * H * 4);
     L->k_pool = take(L->pool_layer_elems * c->n_layers * e);
     L->v_pool = take(L->pool_layer_elems * c->n_layers * e);
     L->kc = take(L->cross_layer_elems * c->n_layers * e);
     L->vc = take(L->cross_layer_elems * c->n_layers * e);
     // every weight matrix once more, in MFMA fragment order
     L->w_frag = take(((size_t)c->n_layers * (8 * d * d + 2 * d * (size_t)c->d_ffn) + (size_t)c->vocab * d) * e);
+    // the batch's encoder states in fragment order (A operand of the cross K/V GEMMs), whole 64-row tiles
+    L->enc_frag = take(align_up((size_t)c->max_total_enc_frames, 64) * d * e);
     L->total = off;
 }
 
 struct GraphKey {
     int batch = -1, n_items = 0, self_chunk = 0, self_nchunks = 0, prompt_len = 0, max_new = 0;
+    long long total_enc = 0;
     bool operator==(const GraphKey& o) const {
-        return batch == o.batch && n_items == o.n_items && self_chunk == o.self_chunk &&
+        return batch == o.batch && n_items == o.n_items && total_enc == o.total_enc && self_chunk == o.self_chunk &&
                self_nchunks == o.self_nchunks && prompt_len == o.prompt_len && max_new == o.max_new;
     }
 };
@@ -184,12 +189,14 @@ aed_status fail(aed_decoder* d, aed_status st, const char* fmt, ...) {
     } while (0)
 
 // Keys per attention work item.  Whole sequences (one workgroup per sequence and
-// head, no merge pass) whenever batch * heads gives the 256 CUs something to do;
-// measured on MI355X, cutting the 24-layer batch-64 workload into 128-key chunks
-// made the attention kernel no faster and added a 4 us merge launch.  Only a
-// batch too small to occupy the GPU (batch * heads < kMinItemsNoSplit) has its
-// long sequences cut, aiming at kTargetItems items of at least 64 keys and at
-// most kMaxChunks per sequence.
+// head, no merge) whenever batch * heads gives the 256 CUs something to do:
+// measured on MI355X, cutting the 24-layer batch-64 and the 4-layer batch-256
+// workloads into 128-key chunks did not shorten the attention kernels (they are
+// bound by the launch's total bytes at the achievable HBM rate plus fixed
+// launch and first-access latency, not by the longest workgroup).  Only a batch
+// too small to occupy the GPU (batch * heads < kMinItemsNoSplit) has its long
+// sequences cut, aiming at kTargetItems items of at least 64 keys and at most
+// kMaxChunks per sequence.
 int pick_chunk(long long total_keys, int max_len, int batch, int n_heads) {
     const long long whole = std::max<long long>(64, ((long long)max_len + 63) / 64 * 64);
     if ((long long)batch * n_heads >= kMinItemsNoSplit) return (int)whole;
@@ -204,6 +211,7 @@ GemmArgs gemm_base(const aed_decoder* d) {
     GemmArgs g;
     memset(&g, 0, sizeof g);
     g.ln_eps = d->cfg.ln_eps;
+    g.ln_scratch = d->ws + d->lay.ln_h;
     g.M = d->batch;
     g.n_heads = d->cfg.n_heads;
     g.head_dim = d->cfg.head_dim;
@@ -234,6 +242,7 @@ AttnArgs attn_base(const aed_decoder* d) {
     a.out = d->ws + d->lay.attn_out;
     a.finished = d->at<int>(d->lay.finished);
     a.part = d->at<float>(d->lay.part);
+    a.counters = d->at<int>(d->lay.counters);
     a.max_chunks = kMaxChunks;
     a.n_heads = d->cfg.n_heads;
     a.head_dim = d->cfg.head_dim;
@@ -306,14 +315,13 @@ hipError_t k_ln_vocab(aed_decoder* d) {
 hipError_t k_cross_kv(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d);
-    g.A = d->last_enc;
-    g.a_row_map = d->last_enc_padded ? d->at<int>(d->lay.row_map) : nullptr;
+    g.A = d->ws + d->lay.enc_frag;
     g.W = d->fw[l].w_ckv; g.bias = w.b_ckv;
     g.M = (int)d->total_enc; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
     g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.t_cap = d->cfg.max_total_enc_frames;
-    return launch_gemm(d->dt, PRO_RM, EPI_CROSSKV, g, d->stream);
+    return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);
 }
 
 hipError_t k_class(aed_decoder* d, int cls, int l) {
@@ -418,6 +426,9 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
 
     StateArgs st = d->state_args(0, 0);
     HIP_TRY(d, launch_reset(st, nullptr, 0, d->stream));
+    // encoder frames -> fragment order once (gathering the valid rows of a padded tensor), then one GEMM per layer
+    HIP_TRY(d, launch_reorder_rows(d->dt, enc, padded ? d->at<int>(d->lay.row_map) : nullptr, d->ws + d->lay.enc_frag,
+                                   (int)total, d->cfg.d_model, d->stream));
     for (int l = 0; l < d->cfg.n_layers; ++l) HIP_TRY(d, k_cross_kv(d, l));
     HIP_TRY(d, hipStreamSynchronize(d->stream));  // host vectors above go out of scope
     d->state = aed_decoder::STEPPING;
@@ -485,6 +496,10 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
             return cleanup(e, "hipEventCreate");
     if ((e = hipEventCreate(&d->t0)) != hipSuccess) return cleanup(e, "hipEventCreate");
     if ((e = hipEventCreate(&d->t1)) != hipSuccess) return cleanup(e, "hipEventCreate");
+
+    // arrival counters of the chunk merge start at zero and return to zero after every launch
+    if ((e = hipMemsetAsync(d->ws + L.counters, 0, (size_t)cfg->max_batch * cfg->n_heads * 4, d->stream)) != hipSuccess)
+        return cleanup(e, "hipMemsetAsync");
     // re-order every weight matrix into fragment order, once
     {
         char* p = d->ws + L.w_frag;
@@ -621,7 +636,7 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
     if (use_graph) {
         GraphKey key;
         key.batch = B; key.n_items = d->n_items; key.self_chunk = d->self_chunk; key.self_nchunks = d->self_nchunks;
-        key.prompt_len = prompt_len; key.max_new = max_new;
+        key.prompt_len = prompt_len; key.max_new = max_new; key.total_enc = d->total_enc;
         if (!d->gexec || !(key == d->gkey)) {
             if (d->gexec) { (void)hipGraphExecDestroy(d->gexec); d->gexec = nullptr; }
             hipGraph_t graph = nullptr;

@@ -18,13 +18,12 @@
 // each instruction covers 4 whole rows (1 KB for bf16 head_dim 128).  The dot
 // products are reduced over the 16 lanes of a DPP row, the running softmax
 // (max, sum, weighted values) is kept per wavefront in base-2 exponent form,
-// the four wavefronts are merged through LDS.  Sequences of this workload are
-// short (at most 500 encoder frames, a few hundred decoded tokens), so one
-// workgroup per (sequence, head) is the normal case; only when the batch is too
-// small to occupy the GPU are long sequences cut into chunks, whose partial
-// (max, sum, values) go to a scratch buffer and are combined in chunk order by
-// a small second kernel (a kernel boundary is far cheaper here than
-// device-scope fences inside the kernel, which write back and invalidate L2).
+// the wavefronts are merged through LDS.  Sequences of this workload are short
+// (at most 500 encoder frames, a few hundred decoded tokens), so one workgroup
+// per (sequence, head) is the normal case.  When the batch is too small to
+// occupy the GPU, long sequences are cut into chunks of keys handled by
+// different workgroups, and the last workgroup of a (sequence, head) to finish
+// combines the partial (max, sum, values) triples in chunk order.
 #include "common.h"
 #include "kernels.h"
 
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     }
     if (lane == 0) { sm_m[wave] = m_run; sm_l[wave] = l_run; }
     __syncthreads();
-    if (tid >= DH) return;
+    const bool owner = tid < DH;  // thread tid owns output element tid of this head
 
     // merge the wavefronts in order (a wavefront without keys has m = -inf, l = 0, acc = 0)
     float m_tot = sm_m[0];
@@ -194,59 +193,67 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     for (int w = 0; w < NW; ++w) {
         const float f = __builtin_amdgcn_exp2f(sm_m[w] - m_tot);
         l_tot += sm_l[w] * f;
-        o += sm_acc[w][tid] * f;
+        if (owner) o += sm_acc[w][tid] * f;
     }
+    T* out = reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + (owner ? tid : 0), H * DH));
     if (n_chunks == 1) {  // the output feeds the next GEMM: fragment order
-        *reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + tid, H * DH)) =
-            from_f32<T>(o / l_tot);
+        if (owner) *out = from_f32<T>(o / l_tot);
         return;
     }
-    // ---- several chunks: publish the partial; attn_merge_kernel combines them in chunk order ----
-    float* __restrict__ my = a.part + ((size_t)(b * H + h) * a.max_chunks + chunk_idx) * (DH + 2);
-    my[tid] = o;
-    if (tid == 0) { my[DH] = m_tot; my[DH + 1] = l_tot; }
-}
 
-// Combines the partial results of the chunks of one (sequence, head) in chunk
-// order (so the result does not depend on scheduling) -- launched only when a
-// launch shape cuts some sequence into more than one chunk.
-template <typename T, int DH, bool SELF>
-__global__ __launch_bounds__(DH) void attn_merge_kernel(AttnArgs a) {
-    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, H = a.n_heads;
-    if (a.finished[b]) return;
-    int total;
-    if constexpr (SELF) total = a.seq_len[b] + 1;
-    else total = a.enc_off[b + 1] - a.enc_off[b];
-    const int n_chunks = (total + a.chunk - 1) / a.chunk;
-    if (n_chunks <= 1) return;  // the attention kernel wrote the final result itself
-    const float* __restrict__ base = a.part + (size_t)(b * H + h) * a.max_chunks * (DH + 2);
-    float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, base[(size_t)c * (DH + 2) + DH]);
-    float L = 0.f, O = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const float* pc = base + (size_t)c * (DH + 2);
-        const float f = __builtin_amdgcn_exp2f(pc[DH] - M);
-        L += pc[DH + 1] * f;
-        O += pc[tid] * f;
+    // ---- several chunks: publish the partial; the last workgroup of this (sequence, head) to arrive
+    // combines all of them in chunk order, so the result does not depend on scheduling.
+    // Partials and the arrival counter are exchanged with relaxed device-scope atomic accesses, which
+    // are performed at the device's coherence point rather than in this XCD's write-back L2.  Every
+    // thread waits for its own stores to complete before the workgroup's arrival is counted, and the
+    // last arriver issues its loads only after it has seen the full count.  (Device-scope fences would
+    // do the same job, but each costs tens of nanoseconds serialised over all workgroups of the
+    // launch: ~60 us per launch measured here.)
+    const int bh = b * H + h;
+    float* my = a.part + ((size_t)bh * a.max_chunks + chunk_idx) * (DH + 2);
+    if (owner) __hip_atomic_store(&my[tid], o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) {
+        __hip_atomic_store(&my[DH], m_tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&my[DH + 1], l_tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    *reinterpret_cast<T*>(static_cast<char*>(a.out) + frag_elem_off<sizeof(T)>(b, h * DH + tid, H * DH)) =
-        from_f32<T>(O / L);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __shared__ int sm_last;
+    __syncthreads();
+    if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_last = (old == n_chunks - 1);
+    }
+    __syncthreads();
+    if (!sm_last) return;
+    float* base = a.part + (size_t)bh * a.max_chunks * (DH + 2);
+    if (owner) {
+        float M = -INFINITY;
+        for (int c = 0; c < n_chunks; ++c)
+            M = fmaxf(M, __hip_atomic_load(&base[(size_t)c * (DH + 2) + DH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        float L = 0.f, O = 0.f;
+        for (int c = 0; c < n_chunks; ++c) {
+            float* pc = base + (size_t)c * (DH + 2);
+            const float f = __builtin_amdgcn_exp2f(
+                __hip_atomic_load(&pc[DH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - M);
+            L += __hip_atomic_load(&pc[DH + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * f;
+            O += __hip_atomic_load(&pc[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * f;
+        }
+        *out = from_f32<T>(O / L);
+    }
+    if (tid == 0) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
 }
 
 // Wavefronts per workgroup: 8 when the launch has few workgroups (the longest
 // sequence sets the kernel's duration), 4 when there are plenty.
 template <typename T, bool SELF>
-static hipError_t launch_dh(const AttnArgs& a, dim3 grid, bool merge, hipStream_t s) {
-    dim3 mgrid(a.n_heads, a.batch);
-    const bool wide = (size_t)grid.x * grid.y * grid.z <= 2048;
+static hipError_t launch_dh(const AttnArgs& a, dim3 grid, hipStream_t s) {
+    const bool wide = (size_t)grid.x * grid.y * grid.z <= 1024;
     if (a.head_dim == 128) {
         if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF, 8>), grid, dim3(512), 0, s, a);
         else hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF, 4>), grid, dim3(256), 0, s, a);
-        if (merge) hipLaunchKernelGGL((attn_merge_kernel<T, 128, SELF>), mgrid, dim3(128), 0, s, a);
     } else if (a.head_dim == 64) {
         if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF, 8>), grid, dim3(512), 0, s, a);
         else hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF, 4>), grid, dim3(256), 0, s, a);
-        if (merge) hipLaunchKernelGGL((attn_merge_kernel<T, 64, SELF>), mgrid, dim3(64), 0, s, a);
     } else {
         return hipErrorInvalidValue;
     }
@@ -257,15 +264,13 @@ hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s) {
     if (a.chunk < 64 || a.chunk % 64 != 0 || a.n_chunks_max < 1 || a.n_chunks_max > a.max_chunks)
         return hipErrorInvalidValue;
     dim3 grid(a.n_heads, a.batch, a.n_chunks_max);
-    const bool merge = a.n_chunks_max > 1;
-    return dt == kBF16 ? launch_dh<bf16_t, true>(a, grid, merge, s) : launch_dh<float, true>(a, grid, merge, s);
+    return dt == kBF16 ? launch_dh<bf16_t, true>(a, grid, s) : launch_dh<float, true>(a, grid, s);
 }
 
 hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s) {
     if (a.chunk < 64 || a.chunk % 64 != 0 || (a.items && a.n_items < a.batch)) return hipErrorInvalidValue;
     dim3 grid(a.n_heads, a.items ? a.n_items : a.batch);
-    const bool merge = a.items != nullptr;
-    return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, merge, s) : launch_dh<float, false>(a, grid, merge, s);
+    return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, s) : launch_dh<float, false>(a, grid, s);
 }
 
 }  // namespace aed

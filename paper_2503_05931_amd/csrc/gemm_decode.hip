@@ -20,9 +20,11 @@
 //   * the weight fragment is the first MFMA operand: lane (r, g) then holds
 //     C[m = r][n = 4 g .. 4 g + 3], four consecutive outputs of one row, which
 //     is one 16-byte (fp32) or 8-byte (bf16) store, also into fragment order.
-// The LayerNorm prologue keeps a wavefront's slice of the fp32 residual rows
-// in registers, gets the row statistics with two LDS exchanges (mean, then
-// centred sum of squares) and normalises in place, so the rows are read once.
+// The LayerNorm prologue (batches up to 128 rows) keeps a wavefront's slice of
+// the fp32 residual rows in registers, gets the row statistics with two LDS
+// exchanges (mean, then centred sum of squares) and normalises in place, so the
+// rows are read once per workgroup.  Larger batches normalise once in a
+// separate small kernel (layernorm_frag_kernel) and stream the result.
 #include "common.h"
 #include "kernels.h"
 
@@ -50,7 +52,17 @@ __device__ __forceinline__ Frag16<float> load_frag(const float* blk, int lane) {
     }
     return f;
 }
-// row-major source: 16 consecutive elements
+__device__ __forceinline__ void store_frag(bf16_t* blk, int lane, const Frag16<bf16_t>& f) {
+    bf16x8* p = reinterpret_cast<bf16x8*>(blk) + lane;
+    p[0] = f.lo;
+    p[64] = f.hi;
+}
+__device__ __forceinline__ void store_frag(float* blk, int lane, const Frag16<float>& f) {
+    f32x4* p = reinterpret_cast<f32x4*>(blk) + lane;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) p[64 * j] = f32x4{f.v[4 * j], f.v[4 * j + 1], f.v[4 * j + 2], f.v[4 * j + 3]};
+}
+// row-major source (LayerNorm gain/shift vectors): 16 consecutive elements
 __device__ __forceinline__ Frag16<bf16_t> load_frag_rm(const bf16_t* p) {
     Frag16<bf16_t> f;
     f.lo = reinterpret_cast<const bf16x8*>(p)[0];
@@ -218,17 +230,6 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         }
     } else {
         const char* __restrict__ A = static_cast<const char*>(a.A);
-        // PRO_RM only: this lane's rows in a row-major source (clamped to the last row)
-        const T* arow[MT];
-        if constexpr (PRO == PRO_RM) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                int m = m0 + mt * 16 + r;
-                m = m < M ? m : M - 1;
-                size_t src = a.a_row_map ? (size_t)a.a_row_map[m] : (size_t)m;
-                arow[mt] = reinterpret_cast<const T*>(A) + src * K + g * 16;
-            }
-        }
         // U blocks are fetched per group, two groups in flight (register double buffer)
         constexpr int U = (MT + NT) <= 2 ? 4 : ((MT + NT) <= 4 ? 2 : 1);
         Frag16<T> af[2][U][MT], wf[2][U][NT];
@@ -240,13 +241,9 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) wf[buf][u][nt] = load_frag(wblk(nt, i), lane);
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        if constexpr (PRO == PRO_RM)
-                            af[buf][u][mt] = load_frag_rm(arow[mt] + (i * 4 + wave) * 64);
-                        else
-                            af[buf][u][mt] = load_frag(
-                                reinterpret_cast<const T*>(A + frag_block_off<ES>((m0 >> 4) + mt, i * 4 + wave, K)), lane);
-                    }
+                    for (int mt = 0; mt < MT; ++mt)
+                        af[buf][u][mt] = load_frag(
+                            reinterpret_cast<const T*>(A + frag_block_off<ES>((m0 >> 4) + mt, i * 4 + wave, K)), lane);
                 }
             }
         };
@@ -320,6 +317,65 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
     }
 }
 
+
+// ---------------------------------------------------------------- LayerNorm to fragment order
+// For batches above kLnFusedMaxM rows the LayerNorm is not fused into the GEMM (every n-tile
+// workgroup would re-read and re-normalise all fp32 rows, and the resident rows starve the big
+// tiles of registers): this kernel writes h = LN(x) once, in the storage type and fragment order,
+// and the GEMM streams it like any other activation.  One workgroup per 16-row tile; the four
+// wavefronts split K exactly as in the GEMM.
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_frag_kernel(const char* __restrict__ X, const T* __restrict__ G,
+                                                             const T* __restrict__ Bt, char* __restrict__ Hout, int K,
+                                                             float eps) {
+    constexpr int ES = sizeof(T);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    const int rt = blockIdx.x, nblk = K >> 8;
+    __shared__ float red[2][4][16];
+    Frag16<float> xs[kMaxLnBlocks];
+#pragma unroll
+    for (int i = 0; i < kMaxLnBlocks; ++i)
+        if (i < nblk) xs[i] = load_frag(reinterpret_cast<const float*>(X + frag_block_off<4>(rt, i * 4 + wave, K)), lane);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxLnBlocks; ++i)
+        if (i < nblk)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s += xs[i].v[e];
+    s = rows4_sum(s);
+    if (g == 0) red[0][wave][r] = s;
+    __syncthreads();
+    const float mean = (red[0][0][r] + red[0][1][r] + red[0][2][r] + red[0][3][r]) / (float)K;
+    s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxLnBlocks; ++i)
+        if (i < nblk)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float c = xs[i].v[e] - mean;
+                s += c * c;
+            }
+    s = rows4_sum(s);
+    if (g == 0) red[1][wave][r] = s;
+    __syncthreads();
+    const float var = (red[1][0][r] + red[1][1][r] + red[1][2][r] + red[1][3][r]) / (float)K;
+    const float rstd = 1.0f / sqrtf(var + eps);
+#pragma unroll
+    for (int i = 0; i < kMaxLnBlocks; ++i) {
+        if (i < nblk) {
+            const int k0 = (i * 4 + wave) * 64 + g * 16;
+            float gam[16], bet[16], y[16];
+            unpack_frag(load_frag_rm(G + k0), gam);
+            unpack_frag(load_frag_rm(Bt + k0), bet);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) y[e] = (xs[i].v[e] - mean) * rstd * gam[e] + bet[e];
+            Frag16<T> f;
+            pack_frag(y, f);
+            store_frag(reinterpret_cast<T*>(Hout + frag_block_off<ES>(rt, i * 4 + wave, K)), lane, f);
+        }
+    }
+}
+
 template <typename T, int PRO, int EPI, int MT, int NT>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     dim3 grid(a.N / (16 * NT), (a.M + 16 * MT - 1) / (16 * MT));
@@ -339,7 +395,8 @@ static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
     int best = 0;
     double best_cost = 1e300;
     long best_wgs = 0;
-    const int n_cands = sizeof(T) == 4 ? 2 : 5;  // float32 fragments are twice as wide: small tiles only
+    // float32 fragments are twice as wide, and the fused LayerNorm keeps its rows in registers: small tiles only
+    const int n_cands = (sizeof(T) == 4 || PRO == PRO_LN) ? 2 : 5;
     for (int c = 0; c < n_cands; ++c) {
         const int bm = 16 * cands[c].mt, bn = 16 * cands[c].nt;
         if (a.N % bn != 0) continue;
@@ -347,22 +404,41 @@ static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
         const double cost = (double)((wgs + 255) / 256) * (bm * a_bytes + bn * w_bytes);
         if (cost < best_cost || (cost == best_cost && wgs < best_wgs)) { best = c; best_cost = cost; best_wgs = wgs; }
     }
-    switch (best) {
-        case 0: return launch_one<T, PRO, EPI, 1, 1>(a, s);
-        case 1: return launch_one<T, PRO, EPI, 2, 2>(a, s);
-        case 2: return launch_one<T, PRO, EPI, 2, 4>(a, s);
-        case 3: return launch_one<T, PRO, EPI, 4, 2>(a, s);
-        default: return launch_one<T, PRO, EPI, 4, 4>(a, s);
+    if (best == 0) return launch_one<T, PRO, EPI, 1, 1>(a, s);
+    if (best == 1) return launch_one<T, PRO, EPI, 2, 2>(a, s);
+    if constexpr (PRO != PRO_LN) {
+        if (best == 2) return launch_one<T, PRO, EPI, 2, 4>(a, s);
+        if (best == 3) return launch_one<T, PRO, EPI, 4, 2>(a, s);
+        return launch_one<T, PRO, EPI, 4, 4>(a, s);
     }
+    return hipErrorInvalidValue;
 }
 
+constexpr int kLnFusedMaxM = 128;
+
 template <typename T>
-static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s) {
+static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hipStream_t s) {
+    GemmArgs a = a0;
+    // fused LayerNorm while one round of 32x32 tiles covers the product; else LayerNorm once, separately
+    if (pro == PRO_LN && a.M > kLnFusedMaxM && (long)((a.M + 31) / 32) * (a.N / 32) > 256) {
+        // two launches: h = LN(x) in fragment order, then the plain streaming GEMM on h
+        if (!a.ln_scratch) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(layernorm_frag_kernel<T>, dim3((a.M + 15) / 16), dim3(256), 0, s,
+                           static_cast<const char*>(a.A), static_cast<const T*>(a.ln_g), static_cast<const T*>(a.ln_b),
+                           static_cast<char*>(a.ln_scratch), a.K, a.ln_eps);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.A = a.ln_scratch;
+        if (epi == EPI_QKV) return launch_tiles<T, PRO_T, EPI_QKV>(a, s);
+        if (epi == EPI_F32) return launch_tiles<T, PRO_T, EPI_F32>(a, s);
+        if (epi == EPI_RELU_T) return launch_tiles<T, PRO_T, EPI_RELU_T>(a, s);
+        return hipErrorInvalidValue;
+    }
     if (pro == PRO_LN && epi == EPI_QKV) return launch_tiles<T, PRO_LN, EPI_QKV>(a, s);
     if (pro == PRO_LN && epi == EPI_F32) return launch_tiles<T, PRO_LN, EPI_F32>(a, s);
     if (pro == PRO_LN && epi == EPI_RELU_T) return launch_tiles<T, PRO_LN, EPI_RELU_T>(a, s);
     if (pro == PRO_T && epi == EPI_RESID) return launch_tiles<T, PRO_T, EPI_RESID>(a, s);
-    if (pro == PRO_RM && epi == EPI_CROSSKV) return launch_tiles<T, PRO_RM, EPI_CROSSKV>(a, s);
+    if (pro == PRO_T && epi == EPI_CROSSKV) return launch_tiles<T, PRO_T, EPI_CROSSKV>(a, s);
     return hipErrorInvalidValue;
 }
 
@@ -385,6 +461,30 @@ __global__ __launch_bounds__(256) void reorder_weight_kernel(const T* __restrict
     const int k = (int)(piece % (K / EPP)) * EPP;
     const f32x4 v = *reinterpret_cast<const f32x4*>(src + (size_t)n * K + k);  // 16 bytes, any type
     *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(n, k, K)) = v;
+}
+
+// dst (fragment order, [M, K]) <- rows of a row-major source, row m taken from src row row_map[m] (or m)
+template <typename T>
+__global__ __launch_bounds__(256) void reorder_rows_kernel(const T* __restrict__ src, const int* __restrict__ row_map,
+                                                           char* __restrict__ dst, int M, int K) {
+    constexpr int ES = sizeof(T), EPP = 16 / ES;
+    const int m = blockIdx.x;
+    const size_t srow = row_map ? (size_t)row_map[m] : (size_t)m;
+    for (int k = threadIdx.x * EPP; k < K; k += 256 * EPP) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(src + srow * K + k);
+        *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(m, k, K)) = v;
+    }
+}
+
+hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, void* dst, int M, int K, hipStream_t s) {
+    if (M < 1 || K % 64 != 0) return hipErrorInvalidValue;
+    if (dt == kBF16)
+        hipLaunchKernelGGL(reorder_rows_kernel<bf16_t>, dim3(M), dim3(256), 0, s, static_cast<const bf16_t*>(src), row_map,
+                           static_cast<char*>(dst), M, K);
+    else
+        hipLaunchKernelGGL(reorder_rows_kernel<float>, dim3(M), dim3(256), 0, s, static_cast<const float*>(src), row_map,
+                           static_cast<char*>(dst), M, K);
+    return hipGetLastError();
 }
 
 hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s) {

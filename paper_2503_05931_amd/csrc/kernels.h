@@ -11,18 +11,17 @@ constexpr int kPage = 16;  // tokens per self-attention KV page
 
 // ---------------------------------------------------------------- decode GEMM
 // C[M,N] = prologue(A)[M,K] . W[N,K]^T (+bias), then an epilogue.
-enum GemmPro { PRO_LN = 0, PRO_T = 1, PRO_RM = 2 };
+enum GemmPro { PRO_LN = 0, PRO_T = 1 };
 enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROSSKV = 4 };
 
 struct GemmArgs {
-    const void* A;        // PRO_LN: float [M,K] (residual stream), fragment order; PRO_T: T [M,K], fragment
-                          // order; PRO_RM: T [rows,K] row-major
-    const int* a_row_map; // PRO_RM only, may be null: A row of output row m is a_row_map[m]
+    const void* A;        // PRO_LN: float [M,K] (residual stream); PRO_T: T [M,K]; both in fragment order
     const void* W;        // T [N,K] in fragment order (launch_reorder_weight)
     const void* bias;     // T [N] or null
     const void* ln_g;     // T [K]  (PRO_LN)
     const void* ln_b;     // T [K]
     float ln_eps;
+    void* ln_scratch;     // T [M,K] fragment order: LN(x) when the LayerNorm runs as its own launch (M > 128)
     int M, N, K;
     void* out;            // EPI_RESID: float [M,N] fragment order, += ; EPI_F32: float [M,N] row-major;
                           // EPI_RELU_T: T [M,N] fragment order; EPI_QKV: float q [M,d_model] row-major
@@ -44,6 +43,8 @@ struct GemmArgs {
 // Returns hipSuccess or the launch error.  Requirements (checked by the caller):
 // K % 256 == 0, N % 64 == 0, PRO_LN: K <= 1024.
 hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s);
+// dst (fragment order [M,K]) <- rows of a row-major source; row m comes from src row row_map[m] (or m); K % 64 == 0
+hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, void* dst, int M, int K, hipStream_t s);
 // dst (fragment order) <- src (row-major [N,K]); N % 16 == 0, K % 64 == 0
 hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s);
 
@@ -69,6 +70,7 @@ struct AttnArgs {
     long long t_cap;
     // split-K merge
     float* part;          // [B*H][max_chunks][Dh+2]
+    int* counters;        // [B*H] arrivals per (sequence, head); zero between launches
     int max_chunks;
     int n_heads, head_dim;
     float scale_log2e;    // log2(e) / sqrt(Dh)

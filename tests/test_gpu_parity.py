@@ -73,11 +73,15 @@ def test_tiny_fp32_teacher_forced_and_greedy(torch_cuda, oracle):
     ("bf16", 512, 4, 128, [1, 2, 129, 500, 77]),
     ("bf16", 1024, 8, 128, [257, 1, 64]),
     ("bf16", 768, 12, 64, [40]),
+    # more than 128 sequences: the LayerNorm runs as its own launch and the GEMMs use the large tiles
+    ("bf16", 256, 4, 64, [1 + (7 * i) % 90 for i in range(150)]),
+    ("fp32", 256, 4, 64, [1 + (11 * i) % 60 for i in range(131)]),
+    ("bf16", 512, 4, 128, [3 + (5 * i) % 40 for i in range(300)]),
 ])
 def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head_dim, enc_lens):
     from tests import gpu_util as G
     wl = unit_workload(dtype, d_model, n_heads, head_dim, enc_lens, seed=len(enc_lens) + d_model)
-    S = 35  # crosses the 16- and 32-token page boundaries
+    S = 35 if len(enc_lens) < 100 else 18  # crosses the 16- (and 32-) token page boundaries
     toks = random_tokens(wl.cfg, len(enc_lens), S, 5)
     ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
     dec = G.make_decoder(wl)
