@@ -18,6 +18,7 @@ using namespace aed;
 
 namespace {
 
+constexpr int kTiledMinM = 512;     // rows from which the cross K/V GEMM uses the LDS-tiled kernel
 constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
 constexpr int kTargetItems = 512;      // work items aimed at per attention launch when sequences are cut
 constexpr int kMinItemsNoSplit = 128;  // batch * heads from which sequences are never cut
@@ -100,8 +101,8 @@ void make_layout(const aed_config* c, Layout* L) {
     L->vc = take(L->cross_layer_elems * c->n_layers * e);
     // every weight matrix once more, in MFMA fragment order
     L->w_frag = take(((size_t)c->n_layers * (8 * d * d + 2 * d * (size_t)c->d_ffn) + (size_t)c->vocab * d) * e);
-    // the batch's encoder states in fragment order (A operand of the cross K/V GEMMs), whole 64-row tiles
-    L->enc_frag = take(align_up((size_t)c->max_total_enc_frames, 64) * d * e);
+    // the batch's encoder states in fragment order (A operand of the cross K/V GEMMs), whole 256-row tiles
+    L->enc_frag = take(align_up((size_t)c->max_total_enc_frames, 256) * d * e);
     L->total = off;
 }
 
@@ -321,6 +322,7 @@ hipError_t k_cross_kv(aed_decoder* d, int l) {
     g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.t_cap = d->cfg.max_total_enc_frames;
+    if (d->dt == kBF16 && g.M >= kTiledMinM && g.N % 128 == 0) return launch_gemm_tiled(EPI_CROSSKV, g, d->stream);
     return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);
 }
 

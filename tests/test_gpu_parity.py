@@ -88,6 +88,13 @@ def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head
     glog, gids = G.forced_logits_gpu(dec, wl, toks)
     err, near = G.check_forced(ref, glog, gids, G.TOL[dtype])
     print(f"{dtype} d={d_model} H={n_heads}x{head_dim}: max |dlogit| = {err:.2e}, near ties {near}")
+    # cross K/V of the first and the last sequence against the oracle (bf16 storage rounds the values)
+    m = oracle.Model(wl.cfg, wl.weights)
+    kv_tol = 1e-4 if dtype == "fp32" else 2e-2
+    for b in (0, len(enc_lens) - 1):
+        Kr, Vr = m.cross_kv(1, wl.subset([b]).enc)
+        Kg, Vg = dec.aed_read_cross_kv(1, b, int(enc_lens[b]))
+        assert np.abs(Kg - Kr).max() < kv_tol and np.abs(Vg - Vr).max() < kv_tol
     # determinism: a second run is bit-identical
     glog2, gids2 = G.forced_logits_gpu(dec, wl, toks)
     assert (glog2 == glog).all() and (gids2 == gids).all()
