@@ -18,7 +18,6 @@ using namespace aed;
 
 namespace {
 
-constexpr int kTiledMinM = 512;     // rows from which the cross K/V GEMM uses the LDS-tiled kernel
 constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
 constexpr int kTargetItems = 512;      // work items aimed at per attention launch when sequences are cut
 constexpr int kMinItemsNoSplit = 128;  // batch * heads from which sequences are never cut
@@ -66,7 +65,7 @@ aed_status check_config(const aed_config* c, std::string& err) {
 void make_layout(const aed_config* c, Layout* L) {
     const size_t e = c->dtype == 1 ? 2 : 4;
     const size_t B = c->max_batch, d = c->d_model, H = c->n_heads, Dh = c->head_dim;
-    const size_t Bp = align_up(B, 64);  // fragment-order activations are read in whole 64-row tiles
+    const size_t Bp = align_up(B, 128);  // fragment-order activations are read in whole tiles of up to 128 rows
     L->max_pages = (c->max_dec_len + kPage - 1) / kPage;
     L->n_pages = c->kv_pages > 0 ? c->kv_pages : (int)(B * L->max_pages);
     L->max_items = c->max_total_enc_frames / 64 + c->max_batch;
@@ -322,8 +321,7 @@ hipError_t k_cross_kv(aed_decoder* d, int l) {
     g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.t_cap = d->cfg.max_total_enc_frames;
-    if (d->dt == kBF16 && g.M >= kTiledMinM && g.N % 128 == 0) return launch_gemm_tiled(EPI_CROSSKV, g, d->stream);
-    return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);
+    return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);  // LDS-tiled kernel from 512 rows (bf16)
 }
 
 hipError_t k_class(aed_decoder* d, int cls, int l) {

@@ -318,6 +318,13 @@ static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
 }
 
 constexpr int kLnFusedMaxM = 128;
+// The LDS-tiled kernel (bf16, 128 x 128 tiles) takes over once its tiles fill the GPU; below that
+// the streaming kernel's 256+ small workgroups are faster (measured at M = 1024: N = 1024 gives 64
+// tiles and 17.8 us against 7.6 us streamed; N = 4096 gives 256 tiles and 23.8 us against 28.4 us).
+constexpr int kTiledMinTiles = 256;
+template <typename T> static bool use_tiled(const GemmArgs& a) {
+    return sizeof(T) == 2 && a.N % 128 == 0 && (long)((a.M + 127) / 128) * (a.N / 128) >= kTiledMinTiles;
+}
 
 template <typename T>
 static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hipStream_t s) {
@@ -332,6 +339,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         a.A = a.ln_scratch;
+        if (use_tiled<T>(a)) return launch_gemm_tiled(epi, a, s);
         if (epi == EPI_QKV) return launch_tiles<T, PRO_T, EPI_QKV>(a, s);
         if (epi == EPI_F32) return launch_tiles<T, PRO_T, EPI_F32>(a, s);
         if (epi == EPI_RELU_T) return launch_tiles<T, PRO_T, EPI_RELU_T>(a, s);
@@ -340,6 +348,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
     if (pro == PRO_LN && epi == EPI_QKV) return launch_tiles<T, PRO_LN, EPI_QKV>(a, s);
     if (pro == PRO_LN && epi == EPI_F32) return launch_tiles<T, PRO_LN, EPI_F32>(a, s);
     if (pro == PRO_LN && epi == EPI_RELU_T) return launch_tiles<T, PRO_LN, EPI_RELU_T>(a, s);
+    if (pro == PRO_T && use_tiled<T>(a)) return launch_gemm_tiled(epi, a, s);
     if (pro == PRO_T && epi == EPI_RESID) return launch_tiles<T, PRO_T, EPI_RESID>(a, s);
     if (pro == PRO_T && epi == EPI_CROSSKV) return launch_tiles<T, PRO_T, EPI_CROSSKV>(a, s);
     return hipErrorInvalidValue;

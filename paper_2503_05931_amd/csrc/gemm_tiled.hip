@@ -162,7 +162,7 @@ static hipError_t launch_tiled_one(const GemmArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// bf16 only; M rows of A padded to a multiple of 256 in memory; N % 128 == 0; K % 64 == 0.
+// bf16 only; A (fragment order) padded to a multiple of 128 rows in memory; N % 128 == 0; K % 64 == 0.
 hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s) {
     if (a.M < 1 || a.N % 128 != 0 || a.K % 64 != 0) return hipErrorInvalidValue;
     // Measured on MI355X for the cross K/V GEMM (K = 1024, N = 2048, bf16), TFLOP/s at M = 7 217 / 512 000:
@@ -170,7 +170,13 @@ hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s) {
     //   128x128, D = 2: 410 / 419 (one workgroup per CU instead of two: registers)
     // Two co-resident workgroups matter more than tile size or prefetch depth: with 64x64 wavefront
     // tiles LDS reads alone need as many cycles as the MFMAs, so a second workgroup fills the gaps.
-    if (epi == EPI_CROSSKV) return launch_tiled_one<EPI_CROSSKV, 4, 4, 1>(a, s);
+    switch (epi) {
+        case EPI_CROSSKV: return launch_tiled_one<EPI_CROSSKV, 4, 4, 1>(a, s);
+        case EPI_QKV: return launch_tiled_one<EPI_QKV, 4, 4, 1>(a, s);
+        case EPI_RESID: return launch_tiled_one<EPI_RESID, 4, 4, 1>(a, s);
+        case EPI_F32: return launch_tiled_one<EPI_F32, 4, 4, 1>(a, s);
+        case EPI_RELU_T: return launch_tiled_one<EPI_RELU_T, 4, 4, 1>(a, s);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -39,11 +39,11 @@ struct GemmArgs {
     long long t_cap;
 };
 
-// Buffers in fragment order must hold a multiple of 64 rows (rows >= M are read, never written).
+// Buffers in fragment order must hold a multiple of 128 rows (rows >= M are read, never written).
 // Returns hipSuccess or the launch error.  Requirements (checked by the caller):
 // K % 256 == 0, N % 64 == 0, PRO_LN: K <= 1024.
 hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s);
-// LDS-tiled MFMA GEMM for large M (bf16 only; fragment-order A padded to a multiple of 256 rows, N % 128 == 0)
+// LDS-tiled MFMA GEMM for large M (bf16 only; fragment-order A padded to a multiple of 128 rows, N % 128 == 0)
 hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s);
 // dst (fragment order [M,K]) <- rows of a row-major source; row m comes from src row row_map[m] (or m); K % 64 == 0
 hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, void* dst, int M, int K, hipStream_t s);

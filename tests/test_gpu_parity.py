@@ -77,6 +77,8 @@ def test_tiny_fp32_teacher_forced_and_greedy(torch_cuda, oracle):
     ("bf16", 256, 4, 64, [1 + (7 * i) % 90 for i in range(150)]),
     ("fp32", 256, 4, 64, [1 + (11 * i) % 60 for i in range(131)]),
     ("bf16", 512, 4, 128, [3 + (5 * i) % 40 for i in range(300)]),
+    # 512 rows and more: every projection runs on the LDS-tiled MFMA kernel (ragged last tile)
+    ("bf16", 256, 4, 64, [2 + (3 * i) % 25 for i in range(530)]),
 ])
 def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head_dim, enc_lens):
     from tests import gpu_util as G
@@ -214,4 +216,24 @@ def test_error_paths_on_device(torch_cuda):
     dec = G.make_decoder(wl, max_batch=2, max_total=20, max_dec_len=32, kv_pages=3)
     dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
     assert status(lambda: dec.aed_greedy_decode(prompt, 20)) == binding.AED_ECAPACITY       # 2 x 2 pages > 3
+    dec.close()
+
+
+def test_tiled_mfma_cross_kv_precompute(torch_cuda, oracle):
+    """Enough encoder frames (2131 x 2048 outputs = 272 tiles of 128 x 128) for the LDS-tiled MFMA kernel,
+    with a ragged last row tile; K and V of every sequence against the oracle, then a few decode steps."""
+    from tests import gpu_util as G
+    enc_lens = [500, 500, 500, 500, 131]
+    wl = unit_workload("bf16", 1024, 8, 128, enc_lens, seed=91, n_layers=1, d_ffn=256, vocab=64, max_new=8)
+    m = oracle.Model(wl.cfg, wl.weights)
+    toks = random_tokens(wl.cfg, 5, 6, 8)
+    ref = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    for b in range(5):
+        Kr, Vr = m.cross_kv(0, wl.subset([b]).enc)
+        Kg, Vg = dec.aed_read_cross_kv(0, b, enc_lens[b])
+        assert np.abs(Kg - Kr).max() < 2e-2 and np.abs(Vg - Vr).max() < 2e-2
+    err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
+    print(f"tiled cross K/V: max |dlogit| = {err:.2e}")
     dec.close()
