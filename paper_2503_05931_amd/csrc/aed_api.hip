@@ -285,7 +285,7 @@ hipError_t k_cross_attn(aed_decoder* d, int l) {
     AttnArgs a = attn_base(d);
     a.K = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     a.V = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
-    a.items = d->n_items > d->batch ? d->at<int4>(d->lay.items) : nullptr;  // list only when some sequence is cut
+    a.items = d->at<int4>(d->lay.items);
     a.n_items = d->n_items;
     a.enc_off = d->at<int>(d->lay.enc_off);
     a.chunk = d->cross_chunk;
@@ -399,6 +399,9 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
         }
     }
     if ((int)items.size() > d->lay.max_items) return fail(d, AED_ECAPACITY, "cross-attention work list overflow");
+    // longest first (stable: equal lengths stay in batch order, so the list is a function of the lengths alone)
+    std::stable_sort(items.begin(), items.end(),
+                     [](const int4& p, const int4& q) { return (p.z & 0xFFFF) > (q.z & 0xFFFF); });
 
     HIP_TRY(d, hipStreamSynchronize(d->stream));  // the previous batch's work is done with the old tables
     HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.enc_off), off.data(), off.size() * 4, hipMemcpyHostToDevice, d->stream));

@@ -7,7 +7,8 @@
 // Work item = (head, sequence, chunk of keys).  Self-attention: the grid's z
 // axis counts chunks and items beyond a sequence's current length exit at
 // once.  Cross-attention: items come from a list built on the host from the
-// true encoder lengths, so neither padding frames nor empty chunks exist.
+// true encoder lengths, longest first, so neither padding frames nor empty
+// chunks exist and the longest sequences are scheduled first.
 //
 // Inside a workgroup (NW = 4 or 8 wavefronts) the chunk is cut into 16-key blocks
 // (= one page of the self-attention cache), wavefront w takes blocks w, w+NW,..
@@ -57,21 +58,27 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
     const int h = blockIdx.x, H = a.n_heads;
 
-    // Work item: with a work list (cross-attention cut into chunks) the item names its sequence and
-    // key range; otherwise blockIdx.y is the sequence, so that the per-sequence scalars below are
-    // all fetched in one round trip.
-    int b, start, n, chunk_idx, n_chunks, row0 = 0;
+    // Work item.  Cross-attention: from the host-built list (longest first, so the long sequences
+    // start early and the short ones fill the tail); the item carries everything needed to address
+    // the keys, so the finished flag, the query and the first key blocks are all fetched in the same
+    // round trip.  Self-attention: blockIdx.y is the sequence, blockIdx.z the chunk.
+    int b, start, n, chunk_idx, n_chunks, row0 = 0, fin;
+    int first_page = 0;  // self-attention: page of this wavefront's first block, fetched with the scalars
     if constexpr (SELF) {
         b = blockIdx.y;
-        const int fin = a.finished[b];
+        fin = a.finished[b];
         const int total = a.seq_len[b] + 1;
+        {
+            const int blk = min((int)(blockIdx.z * a.chunk >> 4) + wave, a.max_pages - 1);
+            first_page = a.page_table[(size_t)b * a.max_pages + blk];
+        }
         if (fin) return;
         n_chunks = (total + a.chunk - 1) / a.chunk;
         chunk_idx = blockIdx.z;
         if (chunk_idx >= n_chunks) return;
         start = chunk_idx * a.chunk;
         n = min(a.chunk, total - start);
-    } else if (a.items) {
+    } else {
         const int4 it = a.items[blockIdx.y];
         b = it.x;
         start = it.y & 0xFFFF;
@@ -79,15 +86,7 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
         n = it.z & 0xFFFF;
         n_chunks = it.z >> 16;
         row0 = it.w + start;  // first frame of this chunk in the packed layout
-        if (a.finished[b]) return;
-    } else {
-        b = blockIdx.y;
-        const int fin = a.finished[b];
-        const int o0 = a.enc_off[b], o1 = a.enc_off[b + 1];
-        if (fin) return;
-        start = 0; chunk_idx = 0; n_chunks = 1;
-        n = o1 - o0;
-        row0 = o0;
+        fin = a.finished[b];  // tested after the first loads have been issued
     }
 
     const T* __restrict__ Kb = static_cast<const T*>(a.K);
@@ -101,7 +100,7 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     // element offset of this lane's slice of key (4 i + g) of block kb (clamped to the valid keys)
     auto fetch = [&](int kb, Raw* kf, Raw* vf) {
         size_t blk_base;
-        if constexpr (SELF) blk_base = ((size_t)pages[kb] * H + h) * kPage * DH;
+        if constexpr (SELF) blk_base = ((size_t)(kb == wave ? first_page : pages[kb]) * H + h) * kPage * DH;
         else blk_base = cross_base + (size_t)kb * 16 * DH;
         const int last = n - 1 - kb * 16;
 #pragma unroll
@@ -160,6 +159,9 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     Raw k0[4], v0[4], k1[4], v1[4];
     int kb = wave;
     if (kb < n_blocks) fetch(kb, k0, v0);
+    if constexpr (!SELF) {
+        if (fin) return;
+    }
     while (kb < n_blocks) {
         if (kb + NW < n_blocks) fetch(kb + NW, k1, v1);
         consume(kb, k0, v0);
@@ -268,8 +270,8 @@ hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s) {
-    if (a.chunk < 64 || a.chunk % 64 != 0 || (a.items && a.n_items < a.batch)) return hipErrorInvalidValue;
-    dim3 grid(a.n_heads, a.items ? a.n_items : a.batch);
+    if (a.chunk < 64 || a.chunk % 64 != 0 || !a.items || a.n_items < a.batch) return hipErrorInvalidValue;
+    dim3 grid(a.n_heads, a.n_items);
     return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, s) : launch_dh<float, false>(a, grid, s);
 }
 

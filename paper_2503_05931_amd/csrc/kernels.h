@@ -65,8 +65,8 @@ struct AttnArgs {
     int n_chunks_max;     // grid.z
     int batch;
     // cross
-    const int4* items;    // null: one item per sequence (no chunking).  Else {b, key_start | chunk_idx << 16,
-                          // n_keys | n_chunks << 16, first frame of b in the packed layout}
+    const int4* items;    // {b, key_start | chunk_idx << 16, n_keys | n_chunks << 16, first frame of b in the
+                          // packed layout}, longest first
     int n_items;
     const int* enc_off;   // [B+1] frame offsets in the packed layout
     long long t_cap;
