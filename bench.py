@@ -165,8 +165,14 @@ def run_ragged(steps, warmup):
         torch.cuda.synchronize()
         return tokens, time.perf_counter() - t0
 
+    # case (b): the library's 2D batch former, 8 duration bins x 2 output-length sub-bins, batches of B
+    from paper_2503_05931_amd import batching
+    former = batching.Bucketing(pe, pd, 8, 2)
+    batch_of, bucket_of_batch = former.aed_bucketing_form_batches(pe, pd, batching.FLEXIBLE, np.full(16, B, np.int32))
+    bucketed = [np.where(batch_of == t)[0] for t in range(len(bucket_of_batch))]
+    bucketed = [x for x in bucketed if len(x) == B]
     cases = {"ragged_random": (W.random_batches(pe, pd, perm, B), False),
-             "bucketed_2d": (W.bucketed_2d_batches(pe, pd, B), False),
+             "bucketed_2d": (bucketed, False),
              "padded_random": (W.random_batches(pe, pd, perm, B), True)}
     out = {}
     for name, (batches, padded) in cases.items():

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaed.so")
 SOURCES = ("aed_api.hip", "gemm_decode.hip", "gemm_tiled.hip", "attn_decode.hip", "step_kernels.hip")
+HOST_SOURCES = ("batching.cpp",)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-pass-failed"]
@@ -36,8 +37,17 @@ def build(verbose: bool = False) -> str:
             print(err)
         return obj
 
+    def compile_host(src):
+        obj = os.path.join(objdir, src.replace(".cpp", ".o"))
+        r = subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-c", os.path.join(CSRC, src), "-o", obj],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"g++ failed for {src}:\n{r.stderr}")
+        return obj
+
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, SOURCES))
+    objs += [compile_host(s) for s in HOST_SOURCES]
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
