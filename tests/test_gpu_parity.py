@@ -18,9 +18,9 @@ def torch_cuda():
 
 
 def unit_workload(dtype, d_model, n_heads, head_dim, enc_lens, seed, n_layers=2, d_ffn=512, vocab=256,
-                  max_new=40, eos_id=-1, **kw):
+                  max_new=40, eos_id=-1, prompt_len=4, **kw):
     cfg = W.DecoderConfig(name="unit", n_layers=n_layers, d_model=d_model, n_heads=n_heads, head_dim=head_dim,
-                          d_ffn=d_ffn, vocab=vocab, dtype=dtype, batch=len(enc_lens), prompt_len=4,
+                          d_ffn=d_ffn, vocab=vocab, dtype=dtype, batch=len(enc_lens), prompt_len=prompt_len,
                           max_new=max_new, eos_id=eos_id, **kw)
     return W.custom(cfg, enc_lens, seed, random_ln=True)
 
@@ -236,4 +236,55 @@ def test_tiled_mfma_cross_kv_precompute(torch_cuda, oracle):
         assert np.abs(Kg - Kr).max() < 2e-2 and np.abs(Vg - Vr).max() < 2e-2
     err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
     print(f"tiled cross K/V: max |dlogit| = {err:.2e}")
+    dec.close()
+
+
+def test_degenerate_shapes_and_reuse(torch_cuda, oracle):
+    """Batch of one, one-token prompt, one new token, a decode length that ends exactly on a page boundary,
+    EOS as the very first token, repeated greedy calls of different lengths on one batch (the launch graph is
+    re-captured), and the step API after a new precompute."""
+    from tests import gpu_util as G
+    torch = torch_cuda
+    tol = G.TOL["fp32"]
+    wl = unit_workload("fp32", 256, 4, 64, [23], seed=41, max_new=31, prompt_len=1)   # 1 + 31 = 32 = two full pages
+    cfg = wl.cfg
+    m = oracle.Model(cfg, wl.weights)
+    dec = G.make_decoder(wl)
+    enc = dec.to_device(wl.enc)
+    prompt = torch.from_numpy(wl.prompt).to(dec.device)
+    assert wl.prompt.shape == (1, 1)
+    for n_new in (1, 31, 16, 31):
+        ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, n_new, want_logits=True)
+        dec.aed_cross_kv_precompute(enc, wl.enc_lens)
+        toks, lens = dec.aed_greedy_decode(prompt, n_new)
+        toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+        first = G.first_near_tie(ref_logits, tol)[0]
+        assert lens[0] == n_new and (toks[0, :first] == ref_t[0, :first]).all()
+    # the cache is exactly full: one more position has no room
+    from paper_2503_05931_amd import binding
+    with pytest.raises(binding.AedError) as ei:
+        dec.aed_greedy_decode(prompt, 32)
+    assert ei.value.status == binding.AED_ECAPACITY
+    dec.close()
+    # EOS as the first emitted token of one sequence: length 1, the rest padding, the other sequence unaffected
+    wl0 = unit_workload("fp32", 256, 4, 64, [9, 14], seed=42, max_new=6)
+    free, _ = oracle.Model(wl0.cfg, wl0.weights).greedy_decode(wl0.enc, wl0.enc_lens, wl0.prompt, 6)
+    eos = int(free[0, 0])
+    wl1 = unit_workload("fp32", 256, 4, 64, [9, 14], seed=42, max_new=6, eos_id=eos, pad_id=1)
+    ref_t, ref_l, ref_logits = oracle.Model(wl1.cfg, wl1.weights).greedy_decode(wl1.enc, wl1.enc_lens, wl1.prompt, 6,
+                                                                               want_logits=True)
+    dec = G.make_decoder(wl1)
+    dec.aed_cross_kv_precompute(dec.to_device(wl1.enc), wl1.enc_lens)
+    toks, lens = dec.aed_greedy_decode(torch.from_numpy(wl1.prompt).to(dec.device), 6)
+    toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+    assert ref_l[0] == 1
+    first = G.first_near_tie(ref_logits[:, :1], tol)
+    if first[0] >= 1:
+        assert lens[0] == 1 and toks[0, 0] == eos and (toks[0, 1:] == 1).all()
+    # step API on a fresh precompute after greedy: teacher-forced logits still match
+    S = 5
+    tk = random_tokens(wl1.cfg, 2, S, 3)
+    ref = oracle.Model(wl1.cfg, wl1.weights).decode_forced(wl1.enc, wl1.enc_lens, tk)
+    glog, gids = G.forced_logits_gpu(dec, wl1, tk)
+    G.check_forced(ref, glog, gids, tol)
     dec.close()
