@@ -222,61 +222,63 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------- LayerNorm to fragment order
-// For batches above kLnFusedMaxM rows the LayerNorm is not fused into the GEMM (every n-tile
-// workgroup would re-read and re-normalise all fp32 rows, and the resident rows starve the big
-// tiles of registers): this kernel writes h = LN(x) once, in the storage type and fragment order,
-// and the GEMM streams it like any other activation.  One workgroup per 16-row tile; the four
-// wavefronts split K exactly as in the GEMM.
+// For larger batches the LayerNorm is not fused into the GEMM (every n-tile workgroup would re-read
+// and re-normalise all fp32 rows, and the resident rows starve the big tiles of registers): this
+// kernel writes h = LN(x) once, in the storage type and fragment order, and the GEMM streams it like
+// any other activation.  One wavefront per row: lane l holds the 16 k values of k-group l (block
+// l / 4, quarter l % 4), the statistics are two wavefront reductions -- no LDS, no barrier -- and
+// M / 4 workgroups spread the rows over the GPU.
 template <typename T>
 __global__ __launch_bounds__(256) void layernorm_frag_kernel(const char* __restrict__ X, const T* __restrict__ G,
-                                                             const T* __restrict__ Bt, char* __restrict__ Hout, int K,
-                                                             float eps) {
+                                                             const T* __restrict__ Bt, char* __restrict__ Hout, int M,
+                                                             int K, float eps) {
     constexpr int ES = sizeof(T);
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const int rt = blockIdx.x, nblk = K >> 8;
-    __shared__ float red[2][4][16];
-    Frag16<float> xs[kMaxLnBlocks];
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const int n_groups = K >> 4;  // 16-wide k groups in a row (K <= 1024: at most 64, one per lane)
+    const bool live = lane < n_groups;
+    const int kb = lane >> 2, q = lane & 3;
+    const int frag_lane = q * 16 + (row & 15);
+    float x[16];
+    if (live) {
+        const f32x4* p = reinterpret_cast<const f32x4*>(X + frag_block_off<4>(row >> 4, kb, K)) + frag_lane;
 #pragma unroll
-    for (int i = 0; i < kMaxLnBlocks; ++i)
-        if (i < nblk) xs[i] = load_frag(reinterpret_cast<const float*>(X + frag_block_off<4>(rt, i * 4 + wave, K)), lane);
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 v = p[64 * j];
+            x[4 * j] = v[0]; x[4 * j + 1] = v[1]; x[4 * j + 2] = v[2]; x[4 * j + 3] = v[3];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) x[e] = 0.f;
+    }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < kMaxLnBlocks; ++i)
-        if (i < nblk)
+    for (int e = 0; e < 16; ++e) s += x[e];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) s += xs[i].v[e];
-    s = rows4_sum(s);
-    if (g == 0) red[0][wave][r] = s;
-    __syncthreads();
-    const float mean = (red[0][0][r] + red[0][1][r] + red[0][2][r] + red[0][3][r]) / (float)K;
-    s = 0.f;
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    const float mean = s / (float)K;
+    float m2 = 0.f;
+    if (live) {
 #pragma unroll
-    for (int i = 0; i < kMaxLnBlocks; ++i)
-        if (i < nblk)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float c = xs[i].v[e] - mean;
-                s += c * c;
-            }
-    s = rows4_sum(s);
-    if (g == 0) red[1][wave][r] = s;
-    __syncthreads();
-    const float var = (red[1][0][r] + red[1][1][r] + red[1][2][r] + red[1][3][r]) / (float)K;
-    const float rstd = 1.0f / sqrtf(var + eps);
-#pragma unroll
-    for (int i = 0; i < kMaxLnBlocks; ++i) {
-        if (i < nblk) {
-            const int k0 = (i * 4 + wave) * 64 + g * 16;
-            float gam[16], bet[16], y[16];
-            unpack_frag(load_frag_rm(G + k0), gam);
-            unpack_frag(load_frag_rm(Bt + k0), bet);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) y[e] = (xs[i].v[e] - mean) * rstd * gam[e] + bet[e];
-            Frag16<T> f;
-            pack_frag(y, f);
-            store_frag(reinterpret_cast<T*>(Hout + frag_block_off<ES>(rt, i * 4 + wave, K)), lane, f);
+        for (int e = 0; e < 16; ++e) {
+            const float c = x[e] - mean;
+            m2 += c * c;
         }
     }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m2 += __shfl_xor(m2, off);
+    const float rstd = 1.0f / sqrtf(m2 / (float)K + eps);
+    if (!live) return;
+    const int k0 = lane * 16;
+    float gam[16], bet[16], y[16];
+    unpack_frag(load_frag_rm(G + k0), gam);
+    unpack_frag(load_frag_rm(Bt + k0), bet);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) y[e] = (x[e] - mean) * rstd * gam[e] + bet[e];
+    Frag16<T> f;
+    pack_frag(y, f);
+    store_frag(reinterpret_cast<T*>(Hout + frag_block_off<ES>(row >> 4, kb, K)), frag_lane, f);
 }
 
 template <typename T, int PRO, int EPI, int MT, int NT>
@@ -333,9 +335,9 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
     if (pro == PRO_LN && a.M > kLnFusedMaxM && (long)((a.M + 31) / 32) * (a.N / 32) > 256) {
         // two launches: h = LN(x) in fragment order, then the plain streaming GEMM on h
         if (!a.ln_scratch) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(layernorm_frag_kernel<T>, dim3((a.M + 15) / 16), dim3(256), 0, s,
+        hipLaunchKernelGGL(layernorm_frag_kernel<T>, dim3((a.M + 3) / 4), dim3(256), 0, s,
                            static_cast<const char*>(a.A), static_cast<const T*>(a.ln_g), static_cast<const T*>(a.ln_b),
-                           static_cast<char*>(a.ln_scratch), a.K, a.ln_eps);
+                           static_cast<char*>(a.ln_scratch), a.M, a.K, a.ln_eps);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         a.A = a.ln_scratch;
