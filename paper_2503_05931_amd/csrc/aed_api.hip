@@ -29,7 +29,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Offsets (bytes) of everything carved from the caller's workspace.
 struct Layout {
     size_t x, q, logits, attn_out, ffn_h, ln_h;
-    size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished;
+    size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished, step_tok;
     size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part, counters;
     size_t k_pool, v_pool, kc, vc, w_frag, enc_frag;
     size_t total;
@@ -86,6 +86,7 @@ void make_layout(const aed_config* c, Layout* L) {
     L->limit = take(B * 4);
     L->limits_in = take(B * 4);
     L->n_finished = take(256);
+    L->step_tok = take(B * 4);
     L->prompt_buf = take(B * (size_t)c->max_dec_len * 4);
     L->out_buf = take(B * (size_t)c->max_dec_len * 4);
     L->page_table = take(B * (size_t)L->max_pages * 4);
@@ -143,8 +144,10 @@ struct aed_decoder {
     int* pin_poll = nullptr;  // pinned host memory for the finished-count poll
     hipEvent_t poll_event[2] = {nullptr, nullptr};
     hipEvent_t t0 = nullptr, t1 = nullptr;
-    hipGraphExec_t gexec = nullptr;
+    hipGraphExec_t gexec = nullptr;       // one greedy step (prompt feeding, EOS rules, output writes)
     GraphKey gkey;
+    hipGraphExec_t step_gexec = nullptr;  // one aed_decode_step step (argmax only, ids into step_tok)
+    GraphKey step_gkey;
     std::string err;
 
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -438,6 +441,26 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     return AED_OK;
 }
 
+// Capture one step (greedy or plain) into a launch graph; an existing graph of the same shape is kept.
+aed_status ensure_graph(aed_decoder* d, const StateArgs& st, int greedy, int* step_out, const GraphKey& key,
+                        hipGraphExec_t* exec, GraphKey* have) {
+    if (*exec && key == *have) return AED_OK;
+    if (*exec) { (void)hipGraphExecDestroy(*exec); *exec = nullptr; }
+    hipGraph_t graph = nullptr;
+    HIP_TRY(d, hipStreamBeginCapture(d->stream, hipStreamCaptureModeThreadLocal));
+    hipError_t e = enqueue_step(d, st, greedy, step_out);
+    hipError_t e2 = hipStreamEndCapture(d->stream, &graph);
+    if (e != hipSuccess || e2 != hipSuccess) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return fail(d, AED_EHIP, "graph capture: %s", hipGetErrorString(e != hipSuccess ? e : e2));
+    }
+    e = hipGraphInstantiate(exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) { *exec = nullptr; return fail(d, AED_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+    *have = key;
+    return AED_OK;
+}
+
 aed_status upload_page_table(aed_decoder* d) {
     HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.page_table), d->page_table.data(), d->page_table.size() * 4,
                               hipMemcpyHostToDevice, d->stream));
@@ -538,6 +561,7 @@ aed_status aed_decoder_destroy(aed_decoder* d) {
     if (!d) return AED_OK;
     (void)hipStreamSynchronize(d->stream);
     if (d->gexec) (void)hipGraphExecDestroy(d->gexec);
+    if (d->step_gexec) (void)hipGraphExecDestroy(d->step_gexec);
     for (int i = 0; i < 2; ++i)
         if (d->poll_event[i]) (void)hipEventDestroy(d->poll_event[i]);
     if (d->t0) (void)hipEventDestroy(d->t0);
@@ -575,7 +599,21 @@ aed_status aed_decode_step(aed_decoder* d, const int32_t* tokens_in, int32_t* to
     }
     StateArgs st = d->state_args(0, 0);
     HIP_TRY(d, launch_set_tokens(st.cur_tok, tokens_in, 1, d->batch, d->stream));
-    HIP_TRY(d, enqueue_step(d, st, 0, tokens_out));
+    if (d->stream != nullptr) {
+        // the step itself is a replayed graph working on the library's own buffers; the caller's
+        // pointers only appear in the small copies around it
+        GraphKey key;
+        key.batch = d->batch; key.n_items = d->n_items; key.self_chunk = d->self_chunk;
+        key.self_nchunks = d->self_nchunks; key.total_enc = d->total_enc;
+        aed_status grc = ensure_graph(d, st, 0, d->at<int>(d->lay.step_tok), key, &d->step_gexec, &d->step_gkey);
+        if (grc != AED_OK) return grc;
+        HIP_TRY(d, hipGraphLaunch(d->step_gexec, d->stream));
+        if (tokens_out)
+            HIP_TRY(d, hipMemcpyAsync(tokens_out, d->at<int>(d->lay.step_tok), (size_t)d->batch * 4,
+                                      hipMemcpyDeviceToDevice, d->stream));
+    } else {
+        HIP_TRY(d, enqueue_step(d, st, 0, tokens_out));
+    }
     if (logits_out)
         HIP_TRY(d, hipMemcpyAsync(logits_out, d->at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4,
                                   hipMemcpyDeviceToDevice, d->stream));
@@ -640,21 +678,8 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
         GraphKey key;
         key.batch = B; key.n_items = d->n_items; key.self_chunk = d->self_chunk; key.self_nchunks = d->self_nchunks;
         key.prompt_len = prompt_len; key.max_new = max_new; key.total_enc = d->total_enc;
-        if (!d->gexec || !(key == d->gkey)) {
-            if (d->gexec) { (void)hipGraphExecDestroy(d->gexec); d->gexec = nullptr; }
-            hipGraph_t graph = nullptr;
-            HIP_TRY(d, hipStreamBeginCapture(d->stream, hipStreamCaptureModeThreadLocal));
-            hipError_t e = enqueue_step(d, st, 1, nullptr);
-            hipError_t e2 = hipStreamEndCapture(d->stream, &graph);
-            if (e != hipSuccess || e2 != hipSuccess) {
-                if (graph) (void)hipGraphDestroy(graph);
-                return fail(d, AED_EHIP, "graph capture: %s", hipGetErrorString(e != hipSuccess ? e : e2));
-            }
-            e = hipGraphInstantiate(&d->gexec, graph, nullptr, nullptr, 0);
-            (void)hipGraphDestroy(graph);
-            if (e != hipSuccess) { d->gexec = nullptr; return fail(d, AED_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
-            d->gkey = key;
-        }
+        aed_status grc = ensure_graph(d, st, 1, nullptr, key, &d->gexec, &d->gkey);
+        if (grc != AED_OK) return grc;
     }
     // Early stop: every poll_every steps the finished count is copied to pinned
     // memory; completed polls are read without blocking, and the host runs at
