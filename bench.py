@@ -187,7 +187,7 @@ def run_ragged(steps, warmup):
     return out, cfg
 
 
-def cpu_baseline(wl, n_seq=16, n_new=32):
+def cpu_baseline(wl, n_seq=16, n_new=96):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     from oracle import aed_oracle as O
     sub = wl.subset(list(range(min(n_seq, len(wl.enc_lens)))))
