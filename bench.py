@@ -126,8 +126,9 @@ def run_workload(name, steps, warmup, want_roofline, eager=False):
 
 def run_ragged(steps, warmup):
     """Ragged-vs-padded stress on the 24-layer decoder, batch 128: the same 2048 samples (a) in random batches,
-    (b) 2D-bucketed into cells of similar (encoder length, output length), and (a) again with every encoder
-    length raised to the batch maximum and no forced end, which is what a padded tensor costs.  Forced EOS at
+    (b) 2D-bucketed into cells of similar (encoder length, output length), (c) as (a) with every encoder
+    length raised to the batch maximum and no forced end, which is what a padded tensor costs, and (d) as one
+    request queue through 128 slots with slot refill.  Forced EOS at
     each sample's target length; tokens counted are the real (unpadded) ones."""
     import numpy as np
     import torch
@@ -183,6 +184,27 @@ def run_ragged(steps, warmup):
         out[name] = {"tokens_per_s": tokens / dt, "batches": len(batches), "tokens": tokens, "seconds": dt,
                      "padding_enc": W.padding_fraction([pe[i] for i in batches]),
                      "padding_dec": W.padding_fraction([pd[i] for i in batches])}
+    # case (d): the same samples as (a), in the same order, as one queue through B slots that are refilled as
+    # sequences end.  The queue call takes every request's encoder states at once (values do not matter for timing).
+    batches = cases["ragged_random"][0]
+    batches = batches[:max(1, steps)] if steps < len(batches) else batches
+    order = np.concatenate(batches)
+    q_lens, q_tgt = pe[order], pd[order]
+    torch.manual_seed(33)
+    q_enc = torch.randn((int(q_lens.sum()), cfg.d_model), device=dec.device, dtype=torch.float32).to(torch.bfloat16)
+    q_prompts = prompts[torch.from_numpy(order).to(dec.device)].contiguous()
+    if warmup:
+        n0 = len(batches[0])
+        dec.aed_greedy_decode_queue(q_enc[:int(q_lens[:n0].sum())], q_lens[:n0], q_prompts[:n0], int(cfg.max_new),
+                                    max_new_per_req=q_tgt[:n0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    _, lens_q, n_steps = dec.aed_greedy_decode_queue(q_enc, q_lens, q_prompts, int(cfg.max_new), max_new_per_req=q_tgt)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tokens = int(np.minimum(q_tgt, lens_q.cpu().numpy()).sum())
+    out["ragged_queue"] = {"tokens_per_s": tokens / dt, "requests": int(len(order)), "slots": int(B), "tokens": tokens,
+                           "seconds": dt, "decoder_steps": n_steps}
     dec.close()
     return out, cfg
 

@@ -27,8 +27,9 @@
  *    the call (everything else).  After aed_decoder_create the library makes
  *    no device allocation; everything it needs is carved from the workspace.
  *  - Streams: all work is enqueued on the stream given at create.  Calls
- *    return after enqueueing, except aed_greedy_decode which polls a
- *    finished-count and synchronises the stream before returning.
+ *    return after enqueueing, except aed_greedy_decode (polls a
+ *    finished-count and synchronises the stream before returning) and
+ *    aed_greedy_decode_queue (blocks until the queue is empty).
  *    One decoder = one stream = one host thread.
  *  - Errors: every call returns an aed_status; argument errors are found on
  *    the host before any launch and leave the decoder unchanged.
@@ -147,6 +148,36 @@ aed_status aed_decode_step(aed_decoder *dec, const int32_t *tokens_in,
 aed_status aed_greedy_decode(aed_decoder *dec, const int32_t *prompt, int32_t prompt_len,
                              int32_t max_new, const int32_t *max_new_per_seq,
                              int32_t *out_tokens, int32_t *out_lens);
+
+/* Greedy decoding of a queue of requests through max_batch slots, with slot
+ * refill: when a sequence finishes, its slot takes the next queued request
+ * instead of idling until the slowest sequence of a fixed batch is done (the
+ * decoded length varies per utterance and the decoder runs one step per
+ * token for the whole batch: Sec. 1; Fig. 3 caption).  Each request's result
+ * is what aed_greedy_decode gives for it in any batch.
+ * A refill computes the new requests' cross-attention K/V (all layers) into
+ * free frames of the cache, re-uses the slot's self-attention pages from
+ * position 0, and hands the finished request's tokens to the caller's rows.
+ * Requests are started in queue order; one that does not fit the free frames
+ * waits for a running one to end.
+ * enc_states: DEVICE [sum(enc_lens), d_model] (all requests, packed);
+ * enc_lens: HOST int32[n_requests]; prompts: DEVICE int32 [n_requests,
+ * prompt_len]; max_new_per_req: HOST int32[n_requests] or NULL (as
+ * max_new_per_seq above); out_tokens: DEVICE int32 [n_requests, max_new],
+ * pad_id after the end; out_lens: DEVICE int32[n_requests]; steps_run: HOST,
+ * may be NULL: decoder steps executed.  Needs eos_id >= 0.  Ends the current
+ * batch, if any (a new aed_cross_kv_precompute is needed for the per-batch
+ * calls).  Blocks until every request is done.
+ * Errors: AED_EINVAL (NULL, n_requests / prompt_len / max_new < 1, an
+ * enc_lens or max_new_per_req entry < 1, eos_id < 0), AED_ECAPACITY
+ * (prompt_len + max_new > max_dec_len or max_positions; a request longer than
+ * max_total_enc_frames; fewer than min(max_batch, n_requests) *
+ * ceil((prompt_len + max_new) / page_size) pages), AED_EUNSUPPORTED (a request
+ * above 65535 frames), AED_EHIP. */
+aed_status aed_greedy_decode_queue(aed_decoder *dec, const void *enc_states, const int32_t *enc_lens,
+                                   int32_t n_requests, const int32_t *prompts, int32_t prompt_len,
+                                   int32_t max_new, const int32_t *max_new_per_req,
+                                   int32_t *out_tokens, int32_t *out_lens, int32_t *steps_run);
 
 /* Message for the most recent error of this decoder (or of the last failed
  * create when dec is NULL).  Owned by the library. */

@@ -26,7 +26,8 @@ KERNEL_NAMES = ["ln_qkv", "self_attn", "self_out", "ln_crossq", "cross_attn", "c
                 "ln_vocab", "sample", "embed", "cross_kv"]
 
 EXPORTS = ("aed_workspace_bytes", "aed_decoder_create", "aed_decoder_destroy", "aed_cross_kv_precompute",
-           "aed_cross_kv_precompute_padded", "aed_decode_step", "aed_greedy_decode", "aed_last_error",
+           "aed_cross_kv_precompute_padded", "aed_decode_step", "aed_greedy_decode", "aed_greedy_decode_queue",
+           "aed_last_error",
            "aed_layer_matrix_params", "aed_read_cross_kv", "aed_read_self_kv", "aed_time_kernels",
            "aed_kernel_work")
 
@@ -72,6 +73,7 @@ def load():
     lib.aed_cross_kv_precompute_padded.argtypes = [vp, vp, C.c_int32, i32p, C.c_int32]
     lib.aed_decode_step.argtypes = [vp, vp, vp, vp]
     lib.aed_greedy_decode.argtypes = [vp, vp, C.c_int32, C.c_int32, i32p, vp, vp]
+    lib.aed_greedy_decode_queue.argtypes = [vp, vp, i32p, C.c_int32, vp, C.c_int32, C.c_int32, i32p, vp, vp, i32p]
     lib.aed_last_error.argtypes = [vp]
     lib.aed_last_error.restype = C.c_char_p
     lib.aed_layer_matrix_params.argtypes = [C.POINTER(AedConfig)]
@@ -235,6 +237,23 @@ class Decoder:
                                                C.c_void_p(out_tokens.data_ptr()), C.c_void_p(out_lens.data_ptr())))
         self._exit()
         return out_tokens, out_lens
+
+    def aed_greedy_decode_queue(self, enc_states, enc_lens, prompts, max_new: int, max_new_per_req=None):
+        """All requests at once: enc_states device [sum(enc_lens), d], prompts device int32 [n, P].
+        Returns (tokens [n, max_new], lens [n], decoder steps run)."""
+        torch = self.torch
+        n, P = prompts.shape
+        out_tokens = torch.empty((n, max_new), dtype=torch.int32, device=self.device)
+        out_lens = torch.empty(n, dtype=torch.int32, device=self.device)
+        lens, plens = _i32_host(enc_lens)
+        mn, pmn = _i32_host(max_new_per_req)
+        steps = C.c_int32(0)
+        self._enter()
+        self._check(self.lib.aed_greedy_decode_queue(
+            self.handle, C.c_void_p(enc_states.data_ptr()), plens, int(n), C.c_void_p(prompts.data_ptr()), int(P),
+            int(max_new), pmn, C.c_void_p(out_tokens.data_ptr()), C.c_void_p(out_lens.data_ptr()), C.byref(steps)))
+        self._exit()
+        return out_tokens, out_lens, int(steps.value)
 
     def aed_read_cross_kv(self, layer: int, seq: int, enc_len: int):
         d = self.cfg.d_model

@@ -30,7 +30,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     size_t x, q, logits, attn_out, ffn_h, ln_h;
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished, step_tok;
-    size_t prompt_buf, out_buf, page_table, enc_off, row_map, items, part, counters;
+    size_t prompt_buf, out_buf, page_table, enc_off, row_map, frame_map, turn_buf, items, part, counters;
     size_t k_pool, v_pool, kc, vc, w_frag, enc_frag;
     size_t total;
     int max_pages, n_pages, max_items;
@@ -92,6 +92,8 @@ void make_layout(const aed_config* c, Layout* L) {
     L->page_table = take(B * (size_t)L->max_pages * 4);
     L->enc_off = take((B + 1) * 4);
     L->row_map = take((size_t)c->max_total_enc_frames * 4);
+    L->frame_map = take((size_t)c->max_total_enc_frames * 4);  // request queue: where each new frame's K/V goes
+    L->turn_buf = take(B * 4 * 4);                            // request queue: slot, old / new request, limit
     L->items = take((size_t)L->max_items * 16);
     L->part = take(B * H * kMaxChunks * (Dh + 2) * 4);
     L->counters = take(B * H * 4);
@@ -315,12 +317,15 @@ hipError_t k_ln_vocab(aed_decoder* d) {
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
 }
 
-hipError_t k_cross_kv(aed_decoder* d, int l) {
+// K/V of rows [0, rows) of the fragment-ordered encoder frames; frame_map (may be null) names the frame slot of
+// each row, else row m is frame m.
+hipError_t k_cross_kv(aed_decoder* d, int l, long long rows, const int* frame_map) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d);
     g.A = d->ws + d->lay.enc_frag;
     g.W = d->fw[l].w_ckv; g.bias = w.b_ckv;
-    g.M = (int)d->total_enc; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
+    g.out_row_map = frame_map;
+    g.M = (int)rows; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
     g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.t_cap = d->cfg.max_total_enc_frames;
@@ -338,7 +343,7 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
         case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model);
         case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
         case AED_K_FFN2: return k_resid(d, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn);
-        case AED_K_CROSS_KV: return k_cross_kv(d, l);
+        case AED_K_CROSS_KV: return k_cross_kv(d, l, d->total_enc, nullptr);
         default: return hipErrorInvalidValue;
     }
 }
@@ -435,7 +440,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     // encoder frames -> fragment order once (gathering the valid rows of a padded tensor), then one GEMM per layer
     HIP_TRY(d, launch_reorder_rows(d->dt, enc, padded ? d->at<int>(d->lay.row_map) : nullptr, d->ws + d->lay.enc_frag,
                                    (int)total, d->cfg.d_model, d->stream));
-    for (int l = 0; l < d->cfg.n_layers; ++l) HIP_TRY(d, k_cross_kv(d, l));
+    for (int l = 0; l < d->cfg.n_layers; ++l) HIP_TRY(d, k_cross_kv(d, l, total, nullptr));
     HIP_TRY(d, hipStreamSynchronize(d->stream));  // host vectors above go out of scope
     d->state = aed_decoder::STEPPING;
     return AED_OK;
@@ -514,7 +519,9 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
         return AED_EHIP;
     };
     hipError_t e;
-    if ((e = hipHostMalloc(reinterpret_cast<void**>(&d->pin_poll), 256, hipHostMallocDefault)) != hipSuccess)
+    // two poll words, then (from word 64) one finished flag per sequence for the request queue
+    if ((e = hipHostMalloc(reinterpret_cast<void**>(&d->pin_poll), 256 + (size_t)cfg->max_batch * 4,
+                           hipHostMallocDefault)) != hipSuccess)
         return cleanup(e, "hipHostMalloc");
     d->pin_poll[0] = d->pin_poll[1] = 0;
     for (int i = 0; i < 2; ++i)
@@ -713,6 +720,202 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
     HIP_TRY(d, hipStreamSynchronize(d->stream));
     return AED_OK;
 }
+
+}  // extern "C"
+
+// ------------------------------------------------------------------ request queue (slot refill)
+namespace {
+
+// First-fit allocator over the frame axis of the cross-attention K/V cache.  Free intervals are kept sorted and
+// merged, so with every request released the whole axis is one interval again.
+struct FrameSpace {
+    std::vector<std::pair<int, int>> free_;  // (start, length), ascending start
+    explicit FrameSpace(int total) { free_.push_back({0, total}); }
+    int take(int n) {
+        for (size_t i = 0; i < free_.size(); ++i)
+            if (free_[i].second >= n) {
+                const int at = free_[i].first;
+                free_[i].first += n;
+                free_[i].second -= n;
+                if (free_[i].second == 0) free_.erase(free_.begin() + i);
+                return at;
+            }
+        return -1;
+    }
+    void give(int at, int n) {
+        size_t i = 0;
+        while (i < free_.size() && free_[i].first < at) ++i;
+        free_.insert(free_.begin() + i, {at, n});
+        if (i + 1 < free_.size() && free_[i].first + free_[i].second == free_[i + 1].first) {
+            free_[i].second += free_[i + 1].second;
+            free_.erase(free_.begin() + i + 1);
+        }
+        if (i > 0 && free_[i - 1].first + free_[i - 1].second == free_[i].first) {
+            free_[i - 1].second += free_[i].second;
+            free_.erase(free_.begin() + i);
+        }
+    }
+};
+
+}  // namespace
+
+extern "C" aed_status aed_greedy_decode_queue(aed_decoder* d, const void* enc_states, const int32_t* enc_lens,
+                                              int32_t n_requests, const int32_t* prompts, int32_t prompt_len,
+                                              int32_t max_new, const int32_t* max_new_per_req, int32_t* out_tokens,
+                                              int32_t* out_lens, int32_t* steps_run) {
+    if (!d) return AED_EINVAL;
+    if (!enc_states || !enc_lens || !prompts || !out_tokens || !out_lens)
+        return fail(d, AED_EINVAL, "enc_states / enc_lens / prompts / out_tokens / out_lens is NULL");
+    if (n_requests < 1) return fail(d, AED_EINVAL, "n_requests must be >= 1");
+    if (prompt_len < 1 || max_new < 1) return fail(d, AED_EINVAL, "prompt_len and max_new must be >= 1");
+    if (d->cfg.eos_id < 0) return fail(d, AED_EINVAL, "the request queue needs eos_id >= 0");
+    const int total_len = prompt_len + max_new;
+    if (total_len > d->cfg.max_dec_len || total_len > d->cfg.max_positions)
+        return fail(d, AED_ECAPACITY, "prompt_len + max_new = %d exceeds max_dec_len %d / max_positions %d", total_len,
+                    d->cfg.max_dec_len, d->cfg.max_positions);
+    const int B = std::min(d->cfg.max_batch, n_requests), MP = d->lay.max_pages;
+    const int need_pages = (total_len + kPage - 1) / kPage;
+    if ((long long)B * need_pages > d->lay.n_pages)
+        return fail(d, AED_ECAPACITY, "self-attention page pool too small: %lld pages needed, %d available",
+                    (long long)B * need_pages, d->lay.n_pages);
+    std::vector<long long> src_off((size_t)n_requests + 1, 0);
+    int max_len = 0;
+    for (int r = 0; r < n_requests; ++r) {
+        if (enc_lens[r] < 1) return fail(d, AED_EINVAL, "enc_lens[%d] = %d (must be >= 1)", r, enc_lens[r]);
+        if (enc_lens[r] > 65535)
+            return fail(d, AED_EUNSUPPORTED, "enc_lens[%d] = %d: more than 65535 frames per sequence", r, enc_lens[r]);
+        if (enc_lens[r] > d->cfg.max_total_enc_frames)
+            return fail(d, AED_ECAPACITY, "enc_lens[%d] = %d > max_total_enc_frames %d", r, enc_lens[r],
+                        d->cfg.max_total_enc_frames);
+        if (max_new_per_req && max_new_per_req[r] < 1) return fail(d, AED_EINVAL, "max_new_per_req[%d] < 1", r);
+        src_off[r + 1] = src_off[r] + enc_lens[r];
+        max_len = std::max(max_len, enc_lens[r]);
+    }
+    if (src_off[n_requests] > INT_MAX) return fail(d, AED_EUNSUPPORTED, "more than 2^31 - 1 encoder frames in the queue");
+
+    // Slot b owns pages [b * need_pages, (b + 1) * need_pages) for the whole run: a refilled slot starts again at
+    // position 0 and overwrites them.  Frames of the cross K/V cache are handed out per request.
+    HIP_TRY(d, hipStreamSynchronize(d->stream));
+    d->state = aed_decoder::NO_BATCH;  // the per-batch inspection calls do not apply to a queue run
+    d->batch = B;
+    d->n_items = B;  // one work item per slot (whole sequences), so that the captured launch shape never changes
+    d->cross_chunk = std::max(64, (max_len + 63) / 64 * 64);
+    d->total_enc = -1;
+    d->page_table.assign((size_t)B * MP, 0);
+    for (int b = 0; b < B; ++b)
+        for (int k = 0; k < need_pages; ++k) d->page_table[(size_t)b * MP + k] = b * need_pages + k;
+    d->pages_used = B * need_pages;
+    aed_status rc = upload_page_table(d);
+    if (rc != AED_OK) return rc;
+    d->self_chunk = pick_chunk((long long)B * total_len, total_len, B, d->cfg.n_heads);
+    d->self_nchunks = (total_len + d->self_chunk - 1) / d->self_chunk;
+    const StateArgs st = d->state_args(prompt_len, max_new);
+    const bool use_graph = d->stream != nullptr;
+    if (use_graph) {
+        GraphKey key;
+        key.batch = B; key.n_items = B; key.self_chunk = d->self_chunk; key.self_nchunks = d->self_nchunks;
+        key.prompt_len = prompt_len; key.max_new = max_new; key.total_enc = -1;
+        if ((rc = ensure_graph(d, st, 1, nullptr, key, &d->gexec, &d->gkey)) != AED_OK) return rc;
+    }
+
+    FrameSpace frames(d->cfg.max_total_enc_frames);
+    std::vector<int> slot_req(B, -1), slot_at(B, 0);  // request in the slot (-1: none), its first frame
+    std::vector<int> done_req(B, -1);                 // finished request whose tokens are still in the slot
+    int next_req = 0, active = 0, n_steps = 0;
+    bool first = true;
+    int* turn = d->at<int>(d->lay.turn_buf);
+    int* flags = d->pin_poll + 64;
+    const int poll_every = 8;
+    std::vector<int> h_turn, h_src, h_dst;
+    std::vector<int4> items(B);
+
+    for (;;) {
+        // ---- turn slots over: hand finished requests out, start queued ones where frames are free (queue order)
+        h_turn.assign((size_t)4 * B, -1);
+        h_src.clear();
+        h_dst.clear();
+        int n_turn = 0;
+        bool queue_blocked = false;
+        for (int b = 0; b < B; ++b) {
+            if (slot_req[b] >= 0) continue;
+            int req = -1;
+            if (next_req < n_requests && !queue_blocked) {
+                const int at = frames.take(enc_lens[next_req]);
+                if (at < 0) queue_blocked = true;  // wait for a running request to release its frames
+                else {
+                    req = next_req++;
+                    slot_req[b] = req;
+                    slot_at[b] = at;
+                    ++active;
+                    for (int t = 0; t < enc_lens[req]; ++t) {
+                        h_src.push_back((int)(src_off[req] + t));
+                        h_dst.push_back(at + t);
+                    }
+                }
+            }
+            if (req < 0 && done_req[b] < 0 && !first) continue;  // a parked slot stays as it is
+            h_turn[n_turn] = b;
+            h_turn[B + n_turn] = done_req[b];
+            h_turn[2 * B + n_turn] = req;
+            h_turn[3 * B + n_turn] = req >= 0 && max_new_per_req ? max_new_per_req[req] : INT_MAX;  // no forced end
+            done_req[b] = -1;
+            ++n_turn;
+        }
+        first = false;
+        if (n_turn > 0) {
+            for (int b = 0; b < B; ++b) {  // a parked slot keeps a valid one-frame item; its workgroups exit early
+                const bool on = slot_req[b] >= 0;
+                items[b].x = b; items[b].y = 0; items[b].z = (on ? enc_lens[slot_req[b]] : 1) | (1 << 16);
+                items[b].w = on ? slot_at[b] : 0;
+            }
+            std::vector<int4> sorted(items);
+            std::stable_sort(sorted.begin(), sorted.end(),
+                             [](const int4& p, const int4& q) { return (p.z & 0xFFFF) > (q.z & 0xFFFF); });
+            HIP_TRY(d, hipMemcpyAsync(turn, h_turn.data(), h_turn.size() * 4, hipMemcpyHostToDevice, d->stream));
+            HIP_TRY(d, hipMemcpyAsync(d->at<int4>(d->lay.items), sorted.data(), sorted.size() * 16, hipMemcpyHostToDevice,
+                                      d->stream));
+            HIP_TRY(d, launch_turn_over_slots(st, turn, turn + B, turn + 2 * B, turn + 3 * B, n_turn, prompts, out_tokens,
+                                              out_lens, d->stream));
+            if (!h_src.empty()) {
+                const long long rows = (long long)h_src.size();
+                HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.row_map), h_src.data(), h_src.size() * 4, hipMemcpyHostToDevice,
+                                          d->stream));
+                HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.frame_map), h_dst.data(), h_dst.size() * 4,
+                                          hipMemcpyHostToDevice, d->stream));
+                HIP_TRY(d, launch_reorder_rows(d->dt, enc_states, d->at<int>(d->lay.row_map), d->ws + d->lay.enc_frag,
+                                               (int)rows, d->cfg.d_model, d->stream));
+                for (int l = 0; l < d->cfg.n_layers; ++l)
+                    HIP_TRY(d, k_cross_kv(d, l, rows, d->at<int>(d->lay.frame_map)));
+            }
+            HIP_TRY(d, hipStreamSynchronize(d->stream));  // the host vectors are re-used
+        }
+        if (active == 0) break;  // nothing running, and then nothing queued either (a free axis fits any request)
+
+        // ---- run steps until a slot finishes; the flags are looked at every poll_every steps
+        bool any = false;
+        while (!any) {
+            for (int s = 0; s < poll_every; ++s) {
+                if (use_graph) HIP_TRY(d, hipGraphLaunch(d->gexec, d->stream));
+                else HIP_TRY(d, enqueue_step(d, st, 1, nullptr));
+            }
+            n_steps += poll_every;
+            HIP_TRY(d, hipMemcpyAsync(flags, st.finished, (size_t)B * 4, hipMemcpyDeviceToHost, d->stream));
+            HIP_TRY(d, hipStreamSynchronize(d->stream));
+            for (int b = 0; b < B; ++b)
+                if (slot_req[b] >= 0 && flags[b]) {
+                    frames.give(slot_at[b], enc_lens[slot_req[b]]);
+                    done_req[b] = slot_req[b];
+                    slot_req[b] = -1;
+                    --active;
+                    any = true;
+                }
+        }
+    }
+    if (steps_run) *steps_run = n_steps;
+    return AED_OK;
+}
+
+extern "C" {
 
 const char* aed_last_error(const aed_decoder* d) { return d ? d->err.c_str() : g_create_error.c_str(); }
 

@@ -108,7 +108,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int m, int n, f
         const int c = n - (which ? d : 0);
         const int h = c / a.head_dim, e = c % a.head_dim;
         T* dst = static_cast<T*>(which ? a.vc : a.kc);
-        store4(dst + ((size_t)h * a.t_cap + m) * a.head_dim + e, s);
+        const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
+        store4(dst + ((size_t)h * a.t_cap + frame) * a.head_dim + e, s);
     }
 }
 

@@ -37,6 +37,7 @@ struct GemmArgs {
     void* kc;
     void* vc;
     long long t_cap;
+    const int* out_row_map;  // EPI_CROSSKV, may be null: frame slot that GEMM row m is written to (default m)
 };
 
 // Buffers in fragment order must hold a multiple of 128 rows (rows >= M are read, never written).
@@ -99,6 +100,15 @@ hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out
 hipError_t launch_set_tokens(int* cur_tok, const int* src, int stride, int batch, hipStream_t s);
 // out[b] = n_gen[b]; dst[b, t] = out_tokens[b, t]
 hipError_t launch_copy_out(const StateArgs& st, int* dst_tokens, int* dst_lens, hipStream_t s);
+
+// Slot turnover of the request queue, one workgroup per entry i: slot slots[i] hands its finished request
+// old_reqs[i] over (tokens up to n_gen, then pad_id, and the length, into row old_reqs[i] of dst_tokens
+// [n_requests, max_new] / dst_lens; -1: nothing to hand over) and starts request new_reqs[i] at position 0 with
+// its prompt row of all_prompts [n_requests, prompt_len] and the limit limits[i] (-1: the slot is parked as
+// finished).
+hipError_t launch_turn_over_slots(const StateArgs& st, const int* slots, const int* old_reqs, const int* new_reqs,
+                                  const int* limits, int n, const int* all_prompts, int* dst_tokens, int* dst_lens,
+                                  hipStream_t s);
 
 // finished[b] = 0, seq_len[b] = clamp(seq_len[b], 0, max_pos): a valid mid-decode state for timing runs
 hipError_t launch_prepare_timing(const StateArgs& st, int max_pos, hipStream_t s);

@@ -148,6 +148,40 @@ hipError_t launch_copy_out(const StateArgs& st, int* dst_tokens, int* dst_lens, 
     return hipGetLastError();
 }
 
+__global__ void turn_over_slots_kernel(StateArgs st, const int* __restrict__ slots, const int* __restrict__ old_reqs,
+                                       const int* __restrict__ new_reqs, const int* __restrict__ limits,
+                                       const int* __restrict__ all_prompts, int* __restrict__ dst_tokens,
+                                       int* __restrict__ dst_lens) {
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const int b = slots[i], old = old_reqs[i], req = new_reqs[i];
+    if (old >= 0) {
+        const int n = st.n_gen[b];
+        for (int t = tid; t < st.max_new; t += blockDim.x)
+            dst_tokens[(size_t)old * st.max_new + t] = t < n ? st.out_tokens[(size_t)b * st.out_stride + t] : st.pad_id;
+        if (tid == 0) dst_lens[old] = n;
+    }
+    __syncthreads();  // n_gen is read above and cleared below
+    if (req >= 0)
+        for (int p = tid; p < st.prompt_len; p += blockDim.x)
+            st.prompt[(size_t)b * st.prompt_stride + p] = all_prompts[(size_t)req * st.prompt_len + p];
+    if (tid == 0) {
+        st.seq_len[b] = 0;
+        st.n_gen[b] = 0;
+        st.finished[b] = req < 0;
+        st.cur_tok[b] = req >= 0 ? all_prompts[(size_t)req * st.prompt_len] : 0;
+        st.limit[b] = req >= 0 ? limits[i] : INT_MAX;
+    }
+}
+
+hipError_t launch_turn_over_slots(const StateArgs& st, const int* slots, const int* old_reqs, const int* new_reqs,
+                                  const int* limits, int n, const int* all_prompts, int* dst_tokens, int* dst_lens,
+                                  hipStream_t s) {
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(turn_over_slots_kernel, dim3(n), dim3(64), 0, s, st, slots, old_reqs, new_reqs, limits,
+                       all_prompts, dst_tokens, dst_lens);
+    return hipGetLastError();
+}
+
 __global__ void prepare_timing_kernel(StateArgs st, int max_pos) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= st.batch) return;
