@@ -325,6 +325,7 @@ hipError_t k_cross_kv(aed_decoder* d, int l, long long rows, const int* frame_ma
     g.A = d->ws + d->lay.enc_frag;
     g.W = d->fw[l].w_ckv; g.bias = w.b_ckv;
     g.out_row_map = frame_map;
+    g.a_rows = (int)align_up((size_t)d->cfg.max_total_enc_frames, 256);
     g.M = (int)rows; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
     g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
     g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;

@@ -328,6 +328,14 @@ template <typename T> static bool use_tiled(const GemmArgs& a) {
     return sizeof(T) == 2 && a.N % 128 == 0 && (long)((a.M + 127) / 128) * (a.N / 128) >= kTiledMinTiles;
 }
 
+// The 256 x 256 direct-to-LDS kernel (cross K/V product only) needs whole 256-row tiles in A and enough
+// tiles to occupy most of the compute units with one workgroup each.
+constexpr int kDmaMinTiles = 160;
+template <typename T> static bool use_dma_crosskv(const GemmArgs& a) {
+    return sizeof(T) == 2 && a.N % 256 == 0 && a.N == 2 * a.d_model && a.K >= 256 &&
+           a.a_rows >= (a.M + 255) / 256 * 256 && (long)((a.M + 255) / 256) * (a.N / 256) >= kDmaMinTiles;
+}
+
 template <typename T>
 static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hipStream_t s) {
     GemmArgs a = a0;
@@ -350,6 +358,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
     if (pro == PRO_LN && epi == EPI_QKV) return launch_tiles<T, PRO_LN, EPI_QKV>(a, s);
     if (pro == PRO_LN && epi == EPI_F32) return launch_tiles<T, PRO_LN, EPI_F32>(a, s);
     if (pro == PRO_LN && epi == EPI_RELU_T) return launch_tiles<T, PRO_LN, EPI_RELU_T>(a, s);
+    if (pro == PRO_T && epi == EPI_CROSSKV && use_dma_crosskv<T>(a)) return launch_gemm_dma_crosskv(a, s);
     if (pro == PRO_T && use_tiled<T>(a)) return launch_gemm_tiled(epi, a, s);
     if (pro == PRO_T && epi == EPI_RESID) return launch_tiles<T, PRO_T, EPI_RESID>(a, s);
     if (pro == PRO_T && epi == EPI_CROSSKV) return launch_tiles<T, PRO_T, EPI_CROSSKV>(a, s);

@@ -1,0 +1,252 @@
+// Persistent 256 x 256 bf16 MFMA GEMM whose operands go from memory straight
+// into LDS (no registers in between), for the cross-attention K/V precompute
+// over all encoder frames of a batch: C[M, 2 d] = A[M, d] . W[2 d, d]^T + b,
+// written as per-head K and V rows.
+//
+// Why a second tiled kernel: with 128 x 128 tiles a compute unit has to take in
+// 64 KB per 1024 MFMA cycles, more than its memory pipeline delivers (measured:
+// about 50 bytes per clock and CU from L2); at 256 x 256 it is 32 KB.
+//
+//  * Both operands are in fragment order, so a 1 KB piece (16 rows x 32 k, one
+//    16-byte fragment slice per lane) is what one wavefront-wide
+//    global_load_lds_dwordx4 moves: lane l's 16 bytes land at LDS base + 16 l,
+//    which is the layout the MFMA operands are read back in.  A k-step is 32 k
+//    = one piece of each of the tile's 32 block rows = 32 KB; the 8 wavefronts
+//    request 4 pieces each.
+//  * Ring of 5 stages (160 KB).  The requests are not visible to the compiler,
+//    so the waits are explicit: vmcnt counts a wavefront's requests in issue
+//    order, each wavefront waits for its own part of step t+1, and the barrier
+//    that follows makes the whole stage visible to everyone.  A wait never
+//    counts on anything but loads issued after the ones it needs, so stores in
+//    flight only make it longer.
+//  * One barrier per k-step.  After it: LDS reads of the second half of step t,
+//    MFMAs of the first half with this wavefront's four requests for step t+4
+//    spread between them (a burst of requests right after the barrier fills the
+//    memory pipeline's queue and stalls every wavefront at its next request),
+//    LDS reads of the first half of step t+1, MFMAs of the second half.
+//  * 32x32x16 MFMAs (they reach the matrix pipeline's peak with one wavefront
+//    per SIMD and four accumulators; the 16x16x32 shape needs four times that).
+//    Wavefront tile 128 (m) x 64 (n); the weight fragment is the first operand,
+//    so a lane holds 4 consecutive n of one output row.
+//  * The workgroup is persistent: it walks its tiles as one stream of k-steps,
+//    so the requests for the next tile are in flight during the epilogue.  The
+//    accumulators of a tile start from the bias.  At the end of a tile each
+//    wavefront turns its accumulators (lane = row) into 128-byte row segments
+//    (lane = 16 bytes of a row) through 4 KB of the stage it has just finished,
+//    so that a store instruction writes 8 full 128-byte lines.
+//  * Tiles are numbered n-fastest and each XCD owns a contiguous run of them
+//    (workgroup ids go round-robin over the 8 XCDs): the workgroups of an XCD
+//    share A row panels and the weight tiles through that XCD's L2.
+#include "common.h"
+#include "kernels.h"
+
+namespace aed {
+
+namespace {
+
+constexpr int kBM = 256, kBN = 256, kStages = 5, kStageBytes = 32768;
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+
+// One request: every lane's 16 bytes at g go to LDS byte (lds_base + 16 * lane).  lds_base is wavefront-uniform.
+__device__ __forceinline__ void load_to_lds16(const void* g, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n" ::"s"(lds_base), "v"(g) : "memory");
+}
+// At most N of this wavefront's memory operations still in flight, its LDS reads done, then the barrier.
+template <int N> __device__ __forceinline__ void wait_loads_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+}  // namespace
+
+__global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
+    constexpr int S = kStages;
+    extern __shared__ __align__(16) char lds[];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 2, wn = wave & 3;  // wavefront tile: rows [128 wm, +128), columns [64 wn, +64)
+    const int r32 = lane & 31, hh = lane >> 5;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const int K = a.K, nk = K >> 5;
+    const int n_mt = (a.M + kBM - 1) / kBM, n_nt = a.N / kBN, total = n_mt * n_nt;
+    const int xcd = blockIdx.x & 7, j_in = blockIdx.x >> 3, per_x = gridDim.x >> 3;
+    const int per_xcd = (total + 7) / 8;
+    const int t_begin = xcd * per_xcd, t_end = min(total, t_begin + per_xcd);
+    const int my_tiles = t_begin + j_in < t_end ? (t_end - (t_begin + j_in) + per_x - 1) / per_x : 0;
+    const int T = my_tiles * nk;  // this workgroup's k-steps
+    if (T == 0) return;
+    const char* __restrict__ A = static_cast<const char*>(a.A);
+    const char* __restrict__ W = static_cast<const char*>(a.W);
+
+    // ---- load cursor: the k-step whose pieces are requested next
+    int ld_ti = 0, ld_ks = 0, ld_slot = 0;
+    const char* gp[4];
+    const size_t row_bytes = (size_t)(K >> 6) * 2048;  // one row of 16-row blocks
+    auto set_tile_ptrs = [&](int ti) {
+        const int tile = t_begin + j_in + ti * per_x;
+        const int tm = tile / n_nt, tn = tile - tm * n_nt;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = wave * 4 + j;  // piece of the stage: 0..15 A block rows, 16..31 W block rows
+            gp[j] = (q < 16 ? A + (size_t)(tm * (kBM / 16) + q) * row_bytes
+                            : W + (size_t)(tn * (kBN / 16) + q - 16) * row_bytes) + lane * 16;
+        }
+    };
+    set_tile_ptrs(0);
+    const unsigned lds_wave = lds0 + wave * 4096;
+    // k-step ks of a tile is the 1 KB piece at byte ks * 1024 of every block row
+    auto request_one = [&](int j) {
+        load_to_lds16(gp[j], __builtin_amdgcn_readfirstlane(lds_wave + ld_slot * kStageBytes) + j * 1024);
+        gp[j] += 1024;
+    };
+    auto request_done = [&]() {
+        ld_slot = ld_slot == S - 1 ? 0 : ld_slot + 1;
+        if (++ld_ks == nk) {
+            ld_ks = 0;
+            ++ld_ti;
+            if (ld_ti < my_tiles) set_tile_ptrs(ld_ti);
+        }
+    };
+
+    // ---- fragments: 32x32x16 takes row (lane & 31) and the 8 k of chunk (2 j + (lane >> 5)) of the piece
+    const int frag_lane = (hh * 16 + (r32 & 15)) * 16 + (r32 >> 4) * 1024;
+    auto read_frags = [&](int slot, int j, bf16x8* wf, bf16x8* af) {
+        const char* st = lds + (size_t)slot * kStageBytes + frag_lane + j * 512;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) wf[nt] = *reinterpret_cast<const bf16x8*>(st + (16 + wn * 4 + nt * 2) * 1024);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) af[mt] = *reinterpret_cast<const bf16x8*>(st + (wm * 8 + mt * 2) * 1024);
+    };
+
+    // ---- accumulators: acc[mt][nt][4 q + e] = C[row 32 mt + r32][column 32 nt + 8 q + 4 hh + e] of the wavefront tile
+    f32x16 acc[4][2];
+    bf16x4 braw[2][4];
+    const bf16_t* __restrict__ bias = static_cast<const bf16_t*>(a.bias);
+    auto load_bias = [&](int ti) {
+        const int tile = t_begin + j_in + ti * per_x;
+        const int tn = tile % n_nt;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                braw[nt][q] = bias ? *reinterpret_cast<const bf16x4*>(bias + tn * kBN + wn * 64 + nt * 32 + 8 * q + 4 * hh)
+                                   : bf16x4{(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+    };
+    auto init_acc = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[mt][nt][i] = (float)braw[nt][i >> 2][i & 3];
+    };
+    load_bias(0);
+    init_acc();
+
+    for (int s = 0; s < S - 1; ++s)
+        if (s < T) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) request_one(j);
+            request_done();
+        }
+    wait_loads_barrier<0>();  // steps 0 .. S-2 have landed
+    bf16x8 wf0[2], af0[4], wf1[2], af1[4];
+    read_frags(0, 0, wf0, af0);
+    int slot = 0, ks = 0, ti = 0;  // compute cursor
+
+    for (int t = 0; t < T; ++t) {
+        // After this barrier step t+1 is complete in LDS and nobody reads the slot of step t-1 any more.
+        // The first S-2 steps of a tile were waited for at the end of the previous tile (or above).
+        if (ks < S - 2) wait_lds_barrier();
+        else if (t + S - 2 < T) wait_loads_barrier<(S - 3) * 4>();  // the requests of steps t+2, t+3 may be in flight
+        else wait_loads_barrier<0>();
+        const bool do_request = t + S - 1 < T;
+        if (ks == nk - 1 && ti + 1 < my_tiles) load_bias(ti + 1);  // long before the stores of the epilogue
+        read_frags(slot, 1, wf1, af1);
+        slot = slot == S - 1 ? 0 : slot + 1;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[nt], af0[mt], acc[mt][nt], 0, 0, 0);
+            if (do_request) request_one(mt);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (do_request) request_done();
+        if (t + 1 < T) read_frags(slot, 0, wf0, af0);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[nt], af1[mt], acc[mt][nt], 0, 0, 0);
+
+        if (++ks == nk) {  // the tile is complete
+            ks = 0;
+            const int tile = t_begin + j_in + ti * per_x;
+            const int tm = tile / n_nt, tn = tile - tm * n_nt;
+            // Everything requested so far has landed (so the stores below may stay in flight over the next
+            // S-2 steps) and every wavefront is done with the slot of this step, 4 KB of which each
+            // wavefront now uses for the transpose.
+            wait_loads_barrier<0>();
+            // the next tile's bias has landed too: say so here, or the compiler waits for it after the stores
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(braw[nt][q]));
+            char* scr = lds + (size_t)(slot == 0 ? S - 1 : slot - 1) * kStageBytes + wave * 4096;
+            // the wavefront's 64 columns are one K or V head (head_dim 64) or half of one (head_dim 128)
+            const int n_wave = tn * kBN + wn * 64;
+            const int which = n_wave >= a.d_model;
+            const int col = n_wave - (which ? a.d_model : 0);
+            const int h = col / a.head_dim, e0 = col % a.head_dim;
+            bf16_t* __restrict__ dst = static_cast<bf16_t*>(which ? a.vc : a.kc) + (size_t)h * a.t_cap * a.head_dim + e0;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = 4 * nt + q;  // 16-byte chunk of the 128-byte row: columns 8 c + 4 hh .. + 3
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[mt][nt][4 * q + e];
+                        *reinterpret_cast<bf16x4*>(scr + r32 * 128 + ((c ^ (r32 & 7)) * 16) + hh * 8) = o;
+                    }
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int row = p * 8 + (lane >> 3), c = lane & 7;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(scr + row * 128 + ((c ^ (row & 7)) * 16));
+                    const int m = tm * kBM + wm * 128 + mt * 32 + row;
+                    if (m < a.M) {
+                        const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
+                        *reinterpret_cast<f32x4*>(dst + frame * a.head_dim + c * 8) = v;
+                    }
+                }
+            }
+            ++ti;
+            init_acc();
+        }
+    }
+}
+
+// bf16, EPI_CROSSKV.  A (fragment order) must hold whole 256-row tiles; N % 256 == 0; K % 64 == 0, K >= 256;
+// head_dim 64 or 128 and d_model a multiple of 64, so that a wavefront's 64 columns stay inside one head.
+hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s) {
+    if (a.M < 1 || a.N % kBN != 0 || a.K % 64 != 0 || a.K < 256 || a.d_model % 64 != 0 ||
+        (a.head_dim != 64 && a.head_dim != 128) || a.N != 2 * a.d_model)
+        return hipErrorInvalidValue;
+    constexpr int kLds = kStages * kStageBytes;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int tiles = ((a.M + kBM - 1) / kBM) * (a.N / kBN);
+    const int grid = tiles >= 256 ? 256 : (tiles + 7) / 8 * 8;  // one workgroup per CU, whole rounds over the XCDs
+    hipLaunchKernelGGL(gemm_dma_crosskv_kernel, dim3(grid), dim3(512), kLds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace aed

@@ -38,6 +38,7 @@ struct GemmArgs {
     void* vc;
     long long t_cap;
     const int* out_row_map;  // EPI_CROSSKV, may be null: frame slot that GEMM row m is written to (default m)
+    int a_rows;              // rows the A buffer holds (0: only the next multiple of 128 above M is promised)
 };
 
 // Buffers in fragment order must hold a multiple of 128 rows (rows >= M are read, never written).
@@ -46,6 +47,8 @@ struct GemmArgs {
 hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s);
 // LDS-tiled MFMA GEMM for large M (bf16 only; fragment-order A padded to a multiple of 128 rows, N % 128 == 0)
 hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s);
+// bf16 cross K/V product with 256 x 256 tiles fed by direct-to-LDS loads; A must hold whole 256-row tiles
+hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s);
 // dst (fragment order [M,K]) <- rows of a row-major source; row m comes from src row row_map[m] (or m); K % 64 == 0
 hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, void* dst, int M, int K, hipStream_t s);
 // dst (fragment order) <- src (row-major [N,K]); N % 16 == 0, K % 64 == 0

@@ -239,6 +239,33 @@ def test_tiled_mfma_cross_kv_precompute(torch_cuda, oracle):
     dec.close()
 
 
+@pytest.mark.parametrize("d_model,n_heads,head_dim,enc_lens", [
+    (1024, 8, 128, [700] * 7 + [411]),      # 5 311 frames: 21 row tiles (the last one ragged) x 8 column tiles of 256
+    (512, 8, 64, [1300] * 7 + [1150]),      # 10 250 frames: 41 x 4 tiles, one head per 64 columns
+])
+def test_direct_to_lds_cross_kv_precompute(torch_cuda, oracle, d_model, n_heads, head_dim, enc_lens):
+    """Enough frames for the persistent 256 x 256 kernel that loads its operands straight into LDS
+    (at least 160 tiles): K and V of every sequence against the oracle, then a few decode steps."""
+    from tests import gpu_util as G
+    wl = unit_workload("bf16", d_model, n_heads, head_dim, enc_lens, seed=93, n_layers=1, d_ffn=256, vocab=64, max_new=8)
+    m = oracle.Model(wl.cfg, wl.weights)
+    B = len(enc_lens)
+    toks = random_tokens(wl.cfg, B, 4, 9)
+    ref = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    worst = 0.0
+    for b in range(B):
+        Kr, Vr = m.cross_kv(0, wl.subset([b]).enc)
+        Kg, Vg = dec.aed_read_cross_kv(0, b, enc_lens[b])
+        assert np.isfinite(Kg).all() and np.isfinite(Vg).all()
+        worst = max(worst, float(np.abs(Kg - Kr).max()), float(np.abs(Vg - Vr).max()))
+    assert worst < 2e-2, f"cross K/V differs by {worst}"
+    err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
+    print(f"direct-to-LDS cross K/V (d {d_model}, head_dim {head_dim}): max |dK,dV| = {worst:.2e}, max |dlogit| = {err:.2e}")
+    dec.close()
+
+
 def test_degenerate_shapes_and_reuse(torch_cuda, oracle):
     """Batch of one, one-token prompt, one new token, a decode length that ends exactly on a page boundary,
     EOS as the very first token, repeated greedy calls of different lengths on one batch (the launch graph is

@@ -18,9 +18,10 @@ def torch_cuda():
     return torch
 
 
-def queue_workload(dtype, n_req, seed, max_new, d_model=256, n_heads=4, head_dim=64, max_enc=130, eos_id=-1, pad_id=0):
+def queue_workload(dtype, n_req, seed, max_new, d_model=256, n_heads=4, head_dim=64, max_enc=130, eos_id=-1, pad_id=0,
+                   min_enc=1):
     rng = np.random.default_rng(seed)
-    enc_lens = rng.integers(1, max_enc + 1, size=n_req)
+    enc_lens = rng.integers(min_enc, max_enc + 1, size=n_req)
     enc_lens[rng.integers(0, n_req)] = max_enc          # the longest length occurs
     cfg = W.DecoderConfig(name="queue", n_layers=2, d_model=d_model, n_heads=n_heads, head_dim=head_dim, d_ffn=512,
                           vocab=256, dtype=dtype, batch=n_req, prompt_len=3, max_new=max_new, eos_id=eos_id,
@@ -88,6 +89,13 @@ def test_queue_frames_scarce(torch_cuda, oracle):
 def test_queue_bf16(torch_cuda, oracle):
     run_queue_case(torch_cuda, oracle, "bf16", n_req=50, slots=16, seed=13, max_new=20, d_model=512, n_heads=4,
                    head_dim=128, max_enc=300)
+
+
+def test_queue_large_refill_through_the_frame_map(torch_cuda, oracle):
+    # the first refill brings in more than 5 120 frames at d_model 1024, so the cross K/V of the new requests go
+    # through the 256 x 256 direct-to-LDS kernel and its frame map
+    run_queue_case(torch_cuda, oracle, "bf16", n_req=36, slots=26, seed=29, max_new=8, d_model=1024, n_heads=8,
+                   head_dim=128, max_enc=300, min_enc=200)
 
 
 def test_queue_fewer_requests_than_slots_and_errors(torch_cuda, oracle):
