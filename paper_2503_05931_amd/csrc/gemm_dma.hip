@@ -23,7 +23,10 @@
 //    MFMAs of the first half with this wavefront's four requests for step t+4
 //    spread between them (a burst of requests right after the barrier fills the
 //    memory pipeline's queue and stalls every wavefront at its next request),
-//    LDS reads of the first half of step t+1, MFMAs of the second half.
+//    LDS reads of the first half of step t+1, MFMAs of the second half.  Every
+//    step is the same straight-line code: with all wavefronts at the same place
+//    after a barrier, any chain of branches before the first MFMA idles the
+//    matrix pipeline (measured: 1 279 -> 1 100 cycles per step of 1 024 MFMA cycles).
 //  * 32x32x16 MFMAs (they reach the matrix pipeline's peak with one wavefront
 //    per SIMD and four accumulators; the 16x16x32 shape needs four times that).
 //    Wavefront tile 128 (m) x 64 (n); the weight fragment is the first operand,
@@ -37,6 +40,8 @@
 //  * Tiles are numbered n-fastest and each XCD owns a contiguous run of them
 //    (workgroup ids go round-robin over the 8 XCDs): the workgroups of an XCD
 //    share A row panels and the weight tiles through that XCD's L2.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -73,13 +78,11 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
     const int per_xcd = (total + 7) / 8;
     const int t_begin = xcd * per_xcd, t_end = min(total, t_begin + per_xcd);
     const int my_tiles = t_begin + j_in < t_end ? (t_end - (t_begin + j_in) + per_x - 1) / per_x : 0;
-    const int T = my_tiles * nk;  // this workgroup's k-steps
-    if (T == 0) return;
+    if (my_tiles == 0) return;
     const char* __restrict__ A = static_cast<const char*>(a.A);
     const char* __restrict__ W = static_cast<const char*>(a.W);
 
-    // ---- load cursor: the k-step whose pieces are requested next
-    int ld_ti = 0, ld_ks = 0, ld_slot = 0;
+    // ---- requests: one pointer per piece this wavefront asks for, and the ring slot of the next request step
     const char* gp[4];
     const size_t row_bytes = (size_t)(K >> 6) * 2048;  // one row of 16-row blocks
     auto set_tile_ptrs = [&](int ti) {
@@ -92,21 +95,14 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
                             : W + (size_t)(tn * (kBN / 16) + q - 16) * row_bytes) + lane * 16;
         }
     };
-    set_tile_ptrs(0);
-    const unsigned lds_wave = lds0 + wave * 4096;
+    const unsigned lds_wave = __builtin_amdgcn_readfirstlane(lds0 + wave * 4096);
+    int ld_slot = 0;
     // k-step ks of a tile is the 1 KB piece at byte ks * 1024 of every block row
     auto request_one = [&](int j) {
-        load_to_lds16(gp[j], __builtin_amdgcn_readfirstlane(lds_wave + ld_slot * kStageBytes) + j * 1024);
+        load_to_lds16(gp[j], lds_wave + ld_slot * kStageBytes + j * 1024);
         gp[j] += 1024;
     };
-    auto request_done = [&]() {
-        ld_slot = ld_slot == S - 1 ? 0 : ld_slot + 1;
-        if (++ld_ks == nk) {
-            ld_ks = 0;
-            ++ld_ti;
-            if (ld_ti < my_tiles) set_tile_ptrs(ld_ti);
-        }
-    };
+    auto request_done = [&]() { ld_slot = ld_slot == S - 1 ? 0 : ld_slot + 1; };
 
     // ---- fragments: 32x32x16 takes row (lane & 31) and the 8 k of chunk (2 j + (lane >> 5)) of the piece
     const int frag_lane = (hh * 16 + (r32 & 15)) * 16 + (r32 >> 4) * 1024;
@@ -142,26 +138,25 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
     };
     load_bias(0);
     init_acc();
-
-    for (int s = 0; s < S - 1; ++s)
-        if (s < T) {
+    set_tile_ptrs(0);
+    for (int s = 0; s < S - 1; ++s) {  // nk >= 8: all inside the first tile
 #pragma unroll
-            for (int j = 0; j < 4; ++j) request_one(j);
-            request_done();
-        }
+        for (int j = 0; j < 4; ++j) request_one(j);
+        request_done();
+    }
     wait_loads_barrier<0>();  // steps 0 .. S-2 have landed
     bf16x8 wf0[2], af0[4], wf1[2], af1[4];
     read_frags(0, 0, wf0, af0);
-    int slot = 0, ks = 0, ti = 0;  // compute cursor
+    int slot = 0;  // slot of the step being computed
 
-    for (int t = 0; t < T; ++t) {
-        // After this barrier step t+1 is complete in LDS and nobody reads the slot of step t-1 any more.
-        // The first S-2 steps of a tile were waited for at the end of the previous tile (or above).
-        if (ks < S - 2) wait_lds_barrier();
-        else if (t + S - 2 < T) wait_loads_barrier<(S - 3) * 4>();  // the requests of steps t+2, t+3 may be in flight
-        else wait_loads_barrier<0>();
-        const bool do_request = t + S - 1 < T;
-        if (ks == nk - 1 && ti + 1 < my_tiles) load_bias(ti + 1);  // long before the stores of the epilogue
+    // One k-step; every step of the kernel is this code.  After the barrier the next step is complete in LDS
+    // and nobody reads the slot of the previous step any more, which the four requests then overwrite.
+    // Nothing but the wait and the barrier stands between the last MFMA of a step and the first of the next:
+    // a chain of branches there leaves the matrix pipeline idle, because all wavefronts are at the same place.
+    auto step = [&](auto waited_before) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (decltype(waited_before)::value) wait_lds_barrier();
+        else wait_loads_barrier<(S - 3) * 4>();  // the requests of the two steps after the next may be in flight
         read_frags(slot, 1, wf1, af1);
         slot = slot == S - 1 ? 0 : slot + 1;
 #pragma unroll
@@ -169,64 +164,78 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf0[nt], af0[mt], acc[mt][nt], 0, 0, 0);
-            if (do_request) request_one(mt);
+            request_one(mt);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (do_request) request_done();
-        if (t + 1 < T) read_frags(slot, 0, wf0, af0);
+        request_done();
+        read_frags(slot, 0, wf0, af0);
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf1[nt], af1[mt], acc[mt][nt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-        if (++ks == nk) {  // the tile is complete
-            ks = 0;
-            const int tile = t_begin + j_in + ti * per_x;
-            const int tm = tile / n_nt, tn = tile - tm * n_nt;
-            // Everything requested so far has landed (so the stores below may stay in flight over the next
-            // S-2 steps) and every wavefront is done with the slot of this step, 4 KB of which each
-            // wavefront now uses for the transpose.
-            wait_loads_barrier<0>();
-            // the next tile's bias has landed too: say so here, or the compiler waits for it after the stores
+    for (int ti = 0; ti < my_tiles; ++ti) {
+        // The requests of a tile's last S-1 steps are for the first steps of the next tile; after the last tile
+        // they fetch that tile's own first steps again (never used), which keeps every step alike.
+        const int ti_next = ti + 1 < my_tiles ? ti + 1 : ti;
+        // the first S-2 steps were waited for at the end of the previous tile (or above)
+#pragma unroll 1
+        for (int ks = 0; ks < S - 2; ++ks) step(std::true_type{});
+#pragma unroll 1
+        for (int ks = S - 2; ks < nk; ++ks) {
+            if (ks == nk - (S - 1)) set_tile_ptrs(ti_next);
+            if (ks == nk - 1) load_bias(ti_next);  // long before the stores of the epilogue
+            step(std::false_type{});
+        }
+
+        // ---- the tile is complete
+        const int tile = t_begin + j_in + ti * per_x;
+        const int tm = tile / n_nt, tn = tile - tm * n_nt;
+        // Everything requested so far has landed (so the stores below may stay in flight over the next S-2
+        // steps) and every wavefront is done with the slot of the last step, 4 KB of which each wavefront
+        // now uses for the transpose.
+        wait_loads_barrier<0>();
+        // the next tile's bias has landed too: say so here, or the compiler waits for it after the stores
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(braw[nt][q]));
+        char* scr = lds + (size_t)(slot == 0 ? S - 1 : slot - 1) * kStageBytes + wave * 4096;
+        // the wavefront's 64 columns are one K or V head (head_dim 64) or half of one (head_dim 128)
+        const int n_wave = tn * kBN + wn * 64;
+        const int which = n_wave >= a.d_model;
+        const int col = n_wave - (which ? a.d_model : 0);
+        const int h = col / a.head_dim, e0 = col % a.head_dim;
+        bf16_t* __restrict__ dst = static_cast<bf16_t*>(which ? a.vc : a.kc) + (size_t)h * a.t_cap * a.head_dim + e0;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) asm volatile("" : "+v"(braw[nt][q]));
-            char* scr = lds + (size_t)(slot == 0 ? S - 1 : slot - 1) * kStageBytes + wave * 4096;
-            // the wavefront's 64 columns are one K or V head (head_dim 64) or half of one (head_dim 128)
-            const int n_wave = tn * kBN + wn * 64;
-            const int which = n_wave >= a.d_model;
-            const int col = n_wave - (which ? a.d_model : 0);
-            const int h = col / a.head_dim, e0 = col % a.head_dim;
-            bf16_t* __restrict__ dst = static_cast<bf16_t*>(which ? a.vc : a.kc) + (size_t)h * a.t_cap * a.head_dim + e0;
+                for (int q = 0; q < 4; ++q) {
+                    const int c = 4 * nt + q;  // 16-byte chunk of the 128-byte row: columns 8 c + 4 hh .. + 3
+                    bf16x4 o;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
+                    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[mt][nt][4 * q + e];
+                    *reinterpret_cast<bf16x4*>(scr + r32 * 128 + ((c ^ (r32 & 7)) * 16) + hh * 8) = o;
+                }
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int c = 4 * nt + q;  // 16-byte chunk of the 128-byte row: columns 8 c + 4 hh .. + 3
-                        bf16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[mt][nt][4 * q + e];
-                        *reinterpret_cast<bf16x4*>(scr + r32 * 128 + ((c ^ (r32 & 7)) * 16) + hh * 8) = o;
-                    }
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const int row = p * 8 + (lane >> 3), c = lane & 7;
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(scr + row * 128 + ((c ^ (row & 7)) * 16));
-                    const int m = tm * kBM + wm * 128 + mt * 32 + row;
-                    if (m < a.M) {
-                        const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
-                        *reinterpret_cast<f32x4*>(dst + frame * a.head_dim + c * 8) = v;
-                    }
+            for (int p = 0; p < 4; ++p) {
+                const int row = p * 8 + (lane >> 3), c = lane & 7;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(scr + row * 128 + ((c ^ (row & 7)) * 16));
+                const int m = tm * kBM + wm * 128 + mt * 32 + row;
+                if (m < a.M) {
+                    const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
+                    *reinterpret_cast<f32x4*>(dst + frame * a.head_dim + c * 8) = v;
                 }
             }
-            ++ti;
-            init_acc();
         }
+        init_acc();
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may land in LDS after the workgroup has ended
 }
 
 // bf16, EPI_CROSSKV.  A (fragment order) must hold whole 256-row tiles; N % 256 == 0; K % 64 == 0, K >= 256;
