@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/aed.h"
+#include "frame_space.h"
 #include "kernels.h"
 
 using namespace aed;
@@ -725,41 +726,6 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
 }  // extern "C"
 
 // ------------------------------------------------------------------ request queue (slot refill)
-namespace {
-
-// First-fit allocator over the frame axis of the cross-attention K/V cache.  Free intervals are kept sorted and
-// merged, so with every request released the whole axis is one interval again.
-struct FrameSpace {
-    std::vector<std::pair<int, int>> free_;  // (start, length), ascending start
-    explicit FrameSpace(int total) { free_.push_back({0, total}); }
-    int take(int n) {
-        for (size_t i = 0; i < free_.size(); ++i)
-            if (free_[i].second >= n) {
-                const int at = free_[i].first;
-                free_[i].first += n;
-                free_[i].second -= n;
-                if (free_[i].second == 0) free_.erase(free_.begin() + i);
-                return at;
-            }
-        return -1;
-    }
-    void give(int at, int n) {
-        size_t i = 0;
-        while (i < free_.size() && free_[i].first < at) ++i;
-        free_.insert(free_.begin() + i, {at, n});
-        if (i + 1 < free_.size() && free_[i].first + free_[i].second == free_[i + 1].first) {
-            free_[i].second += free_[i + 1].second;
-            free_.erase(free_.begin() + i + 1);
-        }
-        if (i > 0 && free_[i - 1].first + free_[i - 1].second == free_[i].first) {
-            free_[i - 1].second += free_[i].second;
-            free_.erase(free_.begin() + i);
-        }
-    }
-};
-
-}  // namespace
-
 extern "C" aed_status aed_greedy_decode_queue(aed_decoder* d, const void* enc_states, const int32_t* enc_lens,
                                               int32_t n_requests, const int32_t* prompts, int32_t prompt_len,
                                               int32_t max_new, const int32_t* max_new_per_req, int32_t* out_tokens,

@@ -1,5 +1,6 @@
 """Host code under AddressSanitizer + UndefinedBehaviorSanitizer: the C oracle (all three decoder
-routines) and the C++ batch former, each through a small native driver.  CPU only."""
+routines), the C++ batch former and the request queue's frame allocator, each through a small native driver.
+CPU only."""
 import os
 import shutil
 import subprocess
@@ -61,6 +62,69 @@ int main() {
     exe = str(tmp_path / "san_batching")
     r = run(["g++", "-std=c++17", *SAN, "-I", ROOT, str(src),
              os.path.join(ROOT, "paper_2503_05931_amd", "csrc", "batching.cpp"), "-o", exe])
+    assert r.returncode == 0, r.stderr
+    r = run([exe])
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "ERROR" not in r.stderr and "runtime error" not in r.stderr, r.stderr
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
+def test_frame_allocator_under_asan_ubsan(tmp_path):
+    """The request queue's frame allocator against a brute-force occupancy map: random takes and gives,
+    no overlap, first fit, and one whole interval again once everything is given back."""
+    src = tmp_path / "frames.cpp"
+    src.write_text(r'''
+#include <cstdio>
+#include <vector>
+#include "paper_2503_05931_amd/csrc/frame_space.h"
+int main() {
+    const int total = 1000;
+    aed::FrameSpace fs(total);
+    std::vector<char> used(total, 0);
+    std::vector<std::pair<int, int>> held;
+    unsigned s = 7;
+    auto rnd = [&](unsigned m) { s = s * 1664525u + 1013904223u; return (s >> 8) % m; };
+    for (int it = 0; it < 20000; ++it) {
+        if (held.empty() || rnd(100) < 55) {
+            const int n = 1 + (int)rnd(rnd(4) == 0 ? 400 : 60);
+            int want = -1;                       // brute force: lowest start of a free run of n
+            for (int a = 0, run = 0; a < total; ++a) {
+                run = used[a] ? 0 : run + 1;
+                if (run == n) { want = a - n + 1; break; }
+            }
+            const int got = fs.take(n);
+            if (got != want) { std::printf("take(%d) = %d, brute force says %d\\n", n, got, want); return 2; }
+            if (got >= 0) {
+                for (int a = got; a < got + n; ++a) { if (used[a]) return 3; used[a] = 1; }
+                held.push_back({got, n});
+            }
+        } else {
+            const size_t k = rnd((unsigned)held.size());
+            for (int a = held[k].first; a < held[k].first + held[k].second; ++a) used[a] = 0;
+            fs.give(held[k].first, held[k].second);
+            held.erase(held.begin() + k);
+        }
+        // the free list is sorted, merged, and equals the occupancy map
+        int free_total = 0, prev_end = -1;
+        for (auto& r : fs.free_runs()) {
+            if (r.second < 1 || r.first <= prev_end) return 4;   // empty run, or touching / overlapping its neighbour
+            for (int a = r.first; a < r.first + r.second; ++a) if (used[a]) return 5;
+            prev_end = r.first + r.second;
+            free_total += r.second;
+        }
+        int want_free = 0;
+        for (int a = 0; a < total; ++a) want_free += !used[a];
+        if (free_total != want_free) return 6;
+    }
+    for (auto& h : held) fs.give(h.first, h.second);
+    if (fs.free_runs().size() != 1 || fs.free_runs()[0].first != 0 || fs.free_runs()[0].second != total) return 7;
+    if (fs.take(total) != 0 || fs.take(1) != -1) return 8;
+    std::printf("ok\\n");
+    return 0;
+}
+''')
+    exe = str(tmp_path / "san_frames")
+    r = run(["g++", "-std=c++17", *SAN, "-I", ROOT, str(src), "-o", exe])
     assert r.returncode == 0, r.stderr
     r = run([exe])
     assert r.returncode == 0, r.stdout + r.stderr
