@@ -29,7 +29,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Offsets (bytes) of everything carved from the caller's workspace.
 struct Layout {
-    size_t x, q, logits, attn_out, ffn_h, ln_h;
+    size_t x, q, logits, attn_out, ffn_h, ln_h, x_shadow, ln_stats, mu_hat, ln_fold;
+    size_t stats_elems;  // float2 per statistics buffer
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished, step_tok;
     size_t prompt_buf, out_buf, page_table, enc_off, row_map, frame_map, turn_buf, items, part, counters;
     size_t k_pool, v_pool, kc, vc, w_frag, enc_frag;
@@ -80,6 +81,13 @@ void make_layout(const aed_config* c, Layout* L) {
     L->attn_out = take(Bp * d * e);
     L->ffn_h = take(Bp * (size_t)c->d_ffn * e);
     L->ln_h = take(Bp * d * e);
+    // bfloat16 mode: LayerNorm folded around the products (shadow of the residual rows, tile statistics in two
+    // buffers that alternate from one residual update to the next, row shifts, folded gain/shift vectors)
+    L->x_shadow = take(Bp * d * e);
+    L->stats_elems = (d / 16) * Bp;
+    L->ln_stats = take(2 * L->stats_elems * 8);
+    L->mu_hat = take(2 * Bp * 4);  // two buffers, alternating like the statistics
+    L->ln_fold = take(((size_t)c->n_layers * (4 * d + (size_t)c->d_ffn) + (size_t)c->vocab) * 2 * 4);
     L->seq_len = take(B * 4);
     L->n_gen = take(B * 4);
     L->finished = take(B * 4);
@@ -129,6 +137,10 @@ struct aed_decoder {
     aed_weights w;
     struct FragWeights { const void *w_qkv, *w_o, *w_cq, *w_ckv, *w_co, *w_ff1, *w_ff2; };
     std::vector<FragWeights> fw;            // the matrices re-ordered into fragment order (workspace)
+    struct LnFold { const float *qkv_c1, *qkv_c2, *cq_c1, *cq_c2, *ff1_c1, *ff1_c2; };
+    std::vector<LnFold> fold;               // bfloat16 mode: W . g and W . b + bias of every LayerNorm product
+    const float *out_c1 = nullptr, *out_c2 = nullptr;
+    int x_par = 0;                          // which statistics buffer describes the current residual rows
     const void* fw_out = nullptr;
     hipStream_t stream;
     char* ws;
@@ -225,6 +237,27 @@ GemmArgs gemm_base(const aed_decoder* d) {
     return g;
 }
 
+// bfloat16 mode: the LayerNorm products read the shadow of the residual rows and their statistics
+bool folded_ln(const aed_decoder* d) { return d->dt == kBF16; }
+float2* stats_buf(const aed_decoder* d, int par) {
+    return reinterpret_cast<float2*>(d->ws + d->lay.ln_stats) + (size_t)par * d->lay.stats_elems;
+}
+float* shift_buf(const aed_decoder* d, int par) {
+    return d->at<float>(d->lay.mu_hat) + (size_t)par * (d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+}
+void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float* c2) {
+    g.A = d->ws + d->lay.x_shadow;
+    // rows of version v (parity p): statistics in buffer p; the shadow was shifted by the mean of version v-1,
+    // which that version's product left in shift buffer p^1; this product leaves the mean of version v in buffer p
+    g.stats_in = stats_buf(d, d->x_par);
+    g.mu_hat_in = shift_buf(d, d->x_par ^ 1);
+    g.mu_hat_out = shift_buf(d, d->x_par);
+    g.ln_c1 = c1;
+    g.ln_c2 = c2;
+    g.stat_tiles = d->cfg.d_model / 16;
+    g.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+}
+
 hipError_t k_ln_qkv(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d);
@@ -238,6 +271,10 @@ hipError_t k_ln_qkv(aed_decoder* d, int l) {
     g.max_pages = d->lay.max_pages;
     g.seq_len = d->at<int>(d->lay.seq_len);
     g.finished = d->at<int>(d->lay.finished);
+    if (folded_ln(d)) {
+        ln_consumer(d, g, d->fold[l].qkv_c1, d->fold[l].qkv_c2);
+        return launch_gemm(d->dt, PRO_LNS, EPI_QKV, g, d->stream);
+    }
     return launch_gemm(d->dt, PRO_LN, EPI_QKV, g, d->stream);
 }
 
@@ -269,11 +306,22 @@ hipError_t k_self_attn(aed_decoder* d, int l) {
     return launch_attn_self(d->dt, a, d->stream);
 }
 
-hipError_t k_resid(aed_decoder* d, const void* A, const void* W, const void* bias, int K) {
+// x += A . W^T + bias; next_g: gain of the LayerNorm that reads x next (its shadow is written with it)
+hipError_t k_resid(aed_decoder* d, const void* A, const void* W, const void* bias, int K, const void* next_g) {
     GemmArgs g = gemm_base(d);
     g.A = A; g.W = W; g.bias = bias;
     g.N = d->cfg.d_model; g.K = K;
     g.out = d->at<float>(d->lay.x);
+    if (folded_ln(d)) {
+        g.stats_out = stats_buf(d, d->x_par ^ 1);
+        g.mu_hat_in = shift_buf(d, d->x_par);  // mean of the rows before the update, left by the product that read them
+        g.shadow_out = d->ws + d->lay.x_shadow;
+        g.shadow_g = next_g;
+        g.stat_tiles = d->cfg.d_model / 16;
+        g.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+        d->x_par ^= 1;
+        return launch_gemm(d->dt, PRO_T, EPI_RESID_S, g, d->stream);
+    }
     return launch_gemm(d->dt, PRO_T, EPI_RESID, g, d->stream);
 }
 
@@ -284,6 +332,10 @@ hipError_t k_ln_crossq(aed_decoder* d, int l) {
     g.W = d->fw[l].w_cq; g.bias = w.b_cq; g.ln_g = w.ln2_g; g.ln_b = w.ln2_b;
     g.N = d->cfg.d_model; g.K = d->cfg.d_model;
     g.out = d->at<float>(d->lay.q);
+    if (folded_ln(d)) {
+        ln_consumer(d, g, d->fold[l].cq_c1, d->fold[l].cq_c2);
+        return launch_gemm(d->dt, PRO_LNS, EPI_F32, g, d->stream);
+    }
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
 }
 
@@ -306,6 +358,10 @@ hipError_t k_ln_ffn1(aed_decoder* d, int l) {
     g.W = d->fw[l].w_ff1; g.bias = w.b_ff1; g.ln_g = w.ln3_g; g.ln_b = w.ln3_b;
     g.N = d->cfg.d_ffn; g.K = d->cfg.d_model;
     g.out = d->ws + d->lay.ffn_h;
+    if (folded_ln(d)) {
+        ln_consumer(d, g, d->fold[l].ff1_c1, d->fold[l].ff1_c2);
+        return launch_gemm(d->dt, PRO_LNS, EPI_RELU_T, g, d->stream);
+    }
     return launch_gemm(d->dt, PRO_LN, EPI_RELU_T, g, d->stream);
 }
 
@@ -315,6 +371,10 @@ hipError_t k_ln_vocab(aed_decoder* d) {
     g.W = d->fw_out; g.bias = d->w.b_out; g.ln_g = d->w.lnf_g; g.ln_b = d->w.lnf_b;
     g.N = d->cfg.vocab; g.K = d->cfg.d_model;
     g.out = d->at<float>(d->lay.logits);
+    if (folded_ln(d)) {
+        ln_consumer(d, g, d->out_c1, d->out_c2);
+        return launch_gemm(d->dt, PRO_LNS, EPI_F32, g, d->stream);
+    }
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
 }
 
@@ -339,12 +399,14 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
     switch (cls) {
         case AED_K_LN_QKV: return k_ln_qkv(d, l);
         case AED_K_SELF_ATTN: return k_self_attn(d, l);
-        case AED_K_SELF_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model);
+        case AED_K_SELF_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model, w.ln2_g);
         case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
         case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
-        case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model);
+        case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model, w.ln3_g);
         case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
-        case AED_K_FFN2: return k_resid(d, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn);
+        case AED_K_FFN2:
+            return k_resid(d, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn,
+                           l + 1 < d->cfg.n_layers ? d->layers[l + 1].ln1_g : d->w.lnf_g);
         case AED_K_CROSS_KV: return k_cross_kv(d, l, d->total_enc, nullptr);
         default: return hipErrorInvalidValue;
     }
@@ -353,8 +415,18 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
 // One decoder step for the whole batch, enqueued on the stream.
 hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* step_out) {
     hipError_t e;
+    ShadowArgs sa;
+    memset(&sa, 0, sizeof sa);
+    if (folded_ln(d)) {
+        d->x_par = 0;
+        sa.shadow = d->ws + d->lay.x_shadow;
+        sa.g = d->layers[0].ln1_g;
+        sa.stats = stats_buf(d, 0);
+        sa.mu_hat = shift_buf(d, 1);  // read as the shift of version 0 by the first product
+        sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+    }
     e = launch_embed(d->dt, d->at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
-                     d->cfg.max_positions, d->cfg.emb_scale, d->stream);
+                     d->cfg.max_positions, d->cfg.emb_scale, sa, d->stream);
     if (e != hipSuccess) return e;
     for (int l = 0; l < d->cfg.n_layers; ++l)
         for (int cls = AED_K_LN_QKV; cls <= AED_K_FFN2; ++cls)
@@ -560,6 +632,27 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
         }
         d->fw_out = put(d->w.w_out, cfg->vocab, dm);
         if (e != hipSuccess) return cleanup(e, "weight re-ordering");
+    }
+    if (folded_ln(d)) {  // W . g and W . b + bias of every product that follows a LayerNorm
+        float* p = reinterpret_cast<float*>(d->ws + L.ln_fold);
+        const int dm = cfg->d_model, F = cfg->d_ffn;
+        e = hipSuccess;
+        auto fold = [&](const void* Wm, const void* gv, const void* bv, const void* bias, int N, const float** c1,
+                        const float** c2) {
+            *c1 = p; *c2 = p + N;
+            if (e == hipSuccess) e = launch_fold_ln(d->dt, Wm, gv, bv, bias, p, p + N, N, dm, d->stream);
+            p += 2 * (size_t)N;
+        };
+        d->fold.resize(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            const aed_layer_weights& x = d->layers[l];
+            aed_decoder::LnFold& f = d->fold[l];
+            fold(x.w_qkv, x.ln1_g, x.ln1_b, x.b_qkv, 3 * dm, &f.qkv_c1, &f.qkv_c2);
+            fold(x.w_cq, x.ln2_g, x.ln2_b, x.b_cq, dm, &f.cq_c1, &f.cq_c2);
+            fold(x.w_ff1, x.ln3_g, x.ln3_b, x.b_ff1, F, &f.ff1_c1, &f.ff1_c2);
+        }
+        fold(d->w.w_out, d->w.lnf_g, d->w.lnf_b, d->w.b_out, cfg->vocab, &d->out_c1, &d->out_c2);
+        if (e != hipSuccess) return cleanup(e, "folding LayerNorm gain and shift into the products");
     }
     if ((e = hipStreamSynchronize(d->stream)) != hipSuccess) return cleanup(e, "hipStreamSynchronize");
     *out = d;
@@ -989,18 +1082,27 @@ aed_status aed_kernel_work(aed_decoder* d, int32_t cls, double* bytes, double* f
     if (!bytes || !flops) return fail(d, AED_EINVAL, "NULL output");
     HIP_TRY(d, hipStreamSynchronize(d->stream));
     const double e = (double)d->esz, B = d->batch, dm = d->cfg.d_model, F = d->cfg.d_ffn, V = d->cfg.vocab;
-    auto gemm = [&](double M, double N, double K, double a_bytes, double out_bytes, double ln) {
-        *bytes = N * K * e + N * e + M * K * a_bytes + M * N * out_bytes + ln * 2 * K * e;
+    // ln: the product follows a LayerNorm.  float32 mode reads the float32 rows and the gain / shift vectors;
+    // bfloat16 mode reads the rows' shadow, their tile statistics and shifts, and the folded vectors c1, c2.
+    // resid: a residual update (float32 rows read and written); bfloat16 mode also writes shadow and statistics.
+    const bool folded = folded_ln(d);
+    const double stats = (dm / 16) * B * 8;
+    auto gemm = [&](double M, double N, double K, double a_bytes, double out_bytes, bool ln, bool resid) {
+        *bytes = N * K * e + M * N * out_bytes;
+        if (!ln) *bytes += N * e + M * K * a_bytes;
+        else if (folded) *bytes += M * K * e + stats + M * 4 + 2 * N * 4;
+        else *bytes += N * e + M * K * 4 + 2 * K * e;
+        if (resid && folded) *bytes += M * N * e + 2 * stats + M * 4 + N * e;
         *flops = 2 * M * N * K;
     };
     switch (cls) {
-        case AED_K_LN_QKV: gemm(B, 3 * dm, dm, 4, 0, 1); *bytes += B * dm * 4 + 2 * B * dm * e; break;
-        case AED_K_SELF_OUT: case AED_K_CROSS_OUT: gemm(B, dm, dm, e, 8, 0); break;
-        case AED_K_LN_CROSSQ: gemm(B, dm, dm, 4, 4, 1); break;
-        case AED_K_LN_FFN1: gemm(B, F, dm, 4, e, 1); break;
-        case AED_K_FFN2: gemm(B, dm, F, e, 8, 0); break;
-        case AED_K_LN_VOCAB: gemm(B, V, dm, 4, 4, 1); break;
-        case AED_K_CROSS_KV: gemm((double)d->total_enc, 2 * dm, dm, e, e, 0); break;
+        case AED_K_LN_QKV: gemm(B, 3 * dm, dm, 4, 0, true, false); *bytes += B * dm * 4 + 2 * B * dm * e; break;
+        case AED_K_SELF_OUT: case AED_K_CROSS_OUT: gemm(B, dm, dm, e, 8, false, true); break;
+        case AED_K_LN_CROSSQ: gemm(B, dm, dm, 4, 4, true, false); break;
+        case AED_K_LN_FFN1: gemm(B, F, dm, 4, e, true, false); break;
+        case AED_K_FFN2: gemm(B, dm, F, e, 8, false, true); break;
+        case AED_K_LN_VOCAB: gemm(B, V, dm, 4, 4, true, false); break;
+        case AED_K_CROSS_KV: gemm((double)d->total_enc, 2 * dm, dm, e, e, false, false); break;
         case AED_K_SELF_ATTN: case AED_K_CROSS_ATTN: {
             double keys = 0;
             if (cls == AED_K_CROSS_ATTN) keys = (double)d->total_enc;

@@ -32,6 +32,7 @@
 namespace aed {
 
 constexpr int kMaxLnBlocks = 4;  // PRO_LN: K <= 4 waves * 4 blocks * 64 = 1024
+constexpr int kMaxStatTilesPerGroup = 16;  // folded LayerNorm: d_model <= 1024 = 4 groups * 16 tiles * 16 columns
 
 template <typename T, int PRO, int EPI, int MT, int NT>
 __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
@@ -60,8 +61,13 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
 
     // Epilogue operands do not depend on the product: fetch them first so their latency
     // overlaps the operand stream.
+    constexpr bool LNS = PRO == PRO_LNS;         // LayerNorm folded around the product (see kernels.h)
+    constexpr bool RS = EPI == EPI_RESID_S;      // residual update that also writes shadow and statistics
+    constexpr bool RES = EPI == EPI_RESID || RS;
     const T* __restrict__ bias = static_cast<const T*>(a.bias);
-    f32x4 e_bias[EP], e_res[EP];
+    f32x4 e_bias[EP], e_res[EP], e_aux[EP];  // e_aux: c1 (LNS) or the next LayerNorm's gain (RS)
+    float e_mu[EP];                          // LNS: the shift this row's shadow was written with; RS: the row's
+                                             // mean before the update = the shift its new shadow is written with
 #pragma unroll
     for (int j = 0; j < EP; ++j) {
         const int idx = tid + 256 * j;
@@ -69,11 +75,58 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         const int m = m0 + (t / NT) * 16 + (l & 15);
         const int n = n0 + (t % NT) * 16 + (l >> 4) * 4;
         const bool live = idx < MT * NT * 64 && m < M;
-        e_bias[j] = (bias && live) ? load4(bias + n) : f32x4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (EPI == EPI_RESID)
+        const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (LNS) {
+            e_bias[j] = live ? *reinterpret_cast<const f32x4*>(a.ln_c2 + n) : zero;
+            e_aux[j] = live ? *reinterpret_cast<const f32x4*>(a.ln_c1 + n) : zero;
+        } else {
+            e_bias[j] = (bias && live) ? load4(bias + n) : zero;
+        }
+        if constexpr (RS) e_aux[j] = live ? load4(static_cast<const T*>(a.shadow_g) + n) : zero;
+        if constexpr (LNS || RS) e_mu[j] = live ? a.mu_hat_in[m] : 0.f;
+        if constexpr (RES)
             e_res[j] = live ? *reinterpret_cast<const f32x4*>(static_cast<const char*>(a.out) + frag_elem_off<4>(m, n, a.N))
-                            : f32x4{0.f, 0.f, 0.f, 0.f};
+                            : zero;
     }
+    float stat_n = 0.f;  // elements behind each of the four partial results of the row statistics
+    // mean and sum of squared deviations of local row rl over all columns, from the four partial results
+    auto row_stats = [&](int rl, float& mu, float& m2) {
+        const float a0 = red[0][0][rl], a1 = red[0][1][rl], a2 = red[0][2][rl], a3 = red[0][3][rl];
+        mu = 0.25f * (a0 + a1 + a2 + a3);
+        const float d0 = a0 - mu, d1 = a1 - mu, d2 = a2 - mu, d3 = a3 - mu;
+        m2 = red[1][0][rl] + red[1][1][rl] + red[1][2][rl] + red[1][3][rl] + stat_n * (d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3);
+    };
+
+    // LNS: statistics of the rows being multiplied: four groups of threads combine a quarter of the 16-column
+    // tiles each; the epilogue combines the four.  The loads go out here, ahead of the operand stream; nothing
+    // waits for them before the stream is through.
+    float2 sv[kMaxStatTilesPerGroup];
+    const int st_row = tid % BM, st_grp = tid / BM, st_per = a.stat_tiles >> 2;
+    if constexpr (LNS) {
+        stat_n = 16.f * (float)st_per;
+        const float2* sp = a.stats_in + (size_t)((st_grp & 3) * st_per) * a.m_stride + (m0 + st_row);
+#pragma unroll
+        for (int t = 0; t < kMaxStatTilesPerGroup; ++t)
+            sv[t] = (t < st_per && st_grp < 4) ? sp[(size_t)t * a.m_stride] : float2{0.f, 0.f};
+    }
+    auto combine_row_stats = [&]() {  // equal-sized parts: mean of the means, then the parts' own sums of squares
+                                      // plus 16 x the squared distances of their means (fixed order, no long chain)
+        float sm = 0.f, sq = 0.f;
+#pragma unroll
+        for (int t = 0; t < kMaxStatTilesPerGroup; ++t) {
+            sm += sv[t].x;  // entries beyond st_per are zero
+            sq += sv[t].y;
+        }
+        const float mean = sm / (float)st_per;
+        float dev = 0.f;
+#pragma unroll
+        for (int t = 0; t < kMaxStatTilesPerGroup; ++t)
+            if (t < st_per) dev += (sv[t].x - mean) * (sv[t].x - mean);
+        if (st_grp < 4) {
+            red[0][st_grp][st_row] = mean;
+            red[1][st_grp][st_row] = sq + 16.f * dev;
+        }
+    };
 
     if constexpr (PRO == PRO_LN) {
         const char* __restrict__ X = static_cast<const char*>(a.A);
@@ -196,6 +249,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         }
     }
 
+    if constexpr (LNS) combine_row_stats();
     // ---- sum the four wavefronts' partial tiles in a fixed order, then the epilogue ----
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -216,8 +270,35 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         const int m = m0 + mt * 16 + (l & 15);
         const int n = n0 + nt * 16 + (l >> 4) * 4;
         if (m >= M) continue;
-        s += e_bias[j];
-        gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
+        if constexpr (LNS) {
+            float mu, m2;
+            row_stats(mt * 16 + (l & 15), mu, m2);
+            const float rstd = 1.0f / sqrtf(m2 / (float)K + a.ln_eps), shift = mu - e_mu[j];
+            s = (s - shift * e_aux[j]) * rstd + e_bias[j];
+            gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
+            if (n == 0) a.mu_hat_out[m] = mu;  // the next residual update shifts its shadow by this
+        } else if constexpr (RS) {
+            const float mu_old = e_mu[j];
+            const f32x4 x = e_res[j] + s + e_bias[j];
+            *reinterpret_cast<f32x4*>(static_cast<char*>(a.out) + frag_elem_off<4>(m, n, a.N)) = x;
+            store4(reinterpret_cast<T*>(static_cast<char*>(a.shadow_out) + frag_elem_off<ES>(m, n, a.N)),
+                   (x - mu_old) * e_aux[j]);
+            // this row's 16 columns of the tile sit in the four lanes l, l ^ 16, l ^ 32, l ^ 48
+            float sum = (x[0] + x[1]) + (x[2] + x[3]);
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            const float tmean = sum * (1.f / 16.f);
+            const f32x4 dv = x - tmean;
+            float q = (dv[0] * dv[0] + dv[1] * dv[1]) + (dv[2] * dv[2] + dv[3] * dv[3]);
+            q += __shfl_xor(q, 16);
+            q += __shfl_xor(q, 32);
+            if ((l >> 4) == 0) {
+                a.stats_out[(size_t)(n >> 4) * a.m_stride + m] = float2{tmean, q};
+            }
+        } else {
+            s += e_bias[j];
+            gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
+        }
     }
 }
 
@@ -302,6 +383,7 @@ static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
     long best_wgs = 0;
     // float32 fragments are twice as wide, and the fused LayerNorm keeps its rows in registers: small tiles only
     const int n_cands = (sizeof(T) == 4 || PRO == PRO_LN) ? 2 : 5;
+    static_assert(PRO != PRO_LNS || sizeof(T) == 2, "the folded LayerNorm is a bfloat16-mode path");
     for (int c = 0; c < n_cands; ++c) {
         const int bm = 16 * cands[c].mt, bn = 16 * cands[c].nt;
         if (a.N % bn != 0) continue;
@@ -355,6 +437,24 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
         if (epi == EPI_RELU_T) return launch_tiles<T, PRO_T, EPI_RELU_T>(a, s);
         return hipErrorInvalidValue;
     }
+    if constexpr (sizeof(T) == 2) {
+        if (pro == PRO_LNS) {
+            if (!a.stats_in || !a.mu_hat_in || !a.mu_hat_out || !a.ln_c1 || !a.ln_c2 || a.stat_tiles < 4 || a.stat_tiles % 4 != 0 ||
+                a.stat_tiles > 4 * kMaxStatTilesPerGroup)
+                return hipErrorInvalidValue;
+            if (use_tiled<T>(a)) return launch_gemm_tiled(epi, a, s);
+            if (epi == EPI_QKV) return launch_tiles<T, PRO_LNS, EPI_QKV>(a, s);
+            if (epi == EPI_F32) return launch_tiles<T, PRO_LNS, EPI_F32>(a, s);
+            if (epi == EPI_RELU_T) return launch_tiles<T, PRO_LNS, EPI_RELU_T>(a, s);
+            return hipErrorInvalidValue;
+        }
+        if (pro == PRO_T && epi == EPI_RESID_S) {
+            if (!a.stats_out || !a.mu_hat_in || !a.shadow_out || !a.shadow_g || a.stat_tiles < 4 ||
+                a.stat_tiles % 4 != 0 || a.stat_tiles * 16 != a.N || a.stat_tiles > 4 * kMaxStatTilesPerGroup)
+                return hipErrorInvalidValue;
+            return launch_tiles<T, PRO_T, EPI_RESID_S>(a, s);
+        }
+    }
     if (pro == PRO_LN && epi == EPI_QKV) return launch_tiles<T, PRO_LN, EPI_QKV>(a, s);
     if (pro == PRO_LN && epi == EPI_F32) return launch_tiles<T, PRO_LN, EPI_F32>(a, s);
     if (pro == PRO_LN && epi == EPI_RELU_T) return launch_tiles<T, PRO_LN, EPI_RELU_T>(a, s);
@@ -369,6 +469,45 @@ hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hi
     if (a.M < 1 || a.K % 256 != 0 || a.N % 64 != 0) return hipErrorInvalidValue;
     if (pro == PRO_LN && a.K > 256 * kMaxLnBlocks) return hipErrorInvalidValue;
     return dt == kBF16 ? launch_typed<bf16_t>(pro, epi, a, s) : launch_typed<float>(pro, epi, a, s);
+}
+
+// ---------------------------------------------------------------- LayerNorm folding (once, at create)
+// One wavefront per output column: c1[n] = sum_k W[n,k] g[k], c2[n] = sum_k W[n,k] b[k] + bias[n].
+template <typename T>
+__global__ __launch_bounds__(256) void fold_ln_kernel(const T* __restrict__ W, const T* __restrict__ g,
+                                                      const T* __restrict__ b, const T* __restrict__ bias,
+                                                      float* __restrict__ c1, float* __restrict__ c2, int N, int K) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    float s1 = 0.f, s2 = 0.f;
+    for (int k = lane; k < K; k += 64) {
+        const float w = (float)W[(size_t)n * K + k];
+        s1 += w * (float)g[k];
+        s2 += w * (float)b[k];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        s1 += __shfl_xor(s1, off);
+        s2 += __shfl_xor(s2, off);
+    }
+    if (lane == 0) {
+        c1[n] = s1;
+        c2[n] = s2 + (bias ? (float)bias[n] : 0.f);
+    }
+}
+
+hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b, const void* bias, float* c1, float* c2,
+                          int N, int K, hipStream_t s) {
+    const dim3 grid((N + 3) / 4);
+    if (dt == kBF16)
+        hipLaunchKernelGGL(fold_ln_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(W),
+                           static_cast<const bf16_t*>(g), static_cast<const bf16_t*>(b),
+                           static_cast<const bf16_t*>(bias), c1, c2, N, K);
+    else
+        hipLaunchKernelGGL(fold_ln_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(W),
+                           static_cast<const float*>(g), static_cast<const float*>(b), static_cast<const float*>(bias),
+                           c1, c2, N, K);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- weight re-ordering

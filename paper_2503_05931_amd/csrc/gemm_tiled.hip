@@ -25,7 +25,7 @@
 
 namespace aed {
 
-template <int EPI, int WM, int WN, int D>
+template <int EPI, int WM, int WN, int D, bool LNS>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
     typedef bf16_t T;
     constexpr int BM = 32 * WM, BN = 32 * WN;
@@ -46,6 +46,33 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
     if (wg >= total) return;  // the grid is rounded up to whole rounds over the XCDs
     const int tile_m = wg / n_nt, tile_n = wg % n_nt;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
+    // LNS (LayerNorm folded around the product, see kernels.h): statistics of this tile's rows, two groups of
+    // threads combine half of the 16-column tiles each; read back after the k loop's last barrier
+    __shared__ float row_stat[2][2][BM];
+    float stat_n = 0.f;
+    if constexpr (LNS) {
+        static_assert(BM == 128, "one thread per row and half");
+        const int row = tid & 127, grp = tid >> 7, per = a.stat_tiles >> 1;
+        stat_n = 16.f * (float)per;
+        const float2* sp = a.stats_in + (size_t)(grp * per) * a.m_stride + (m0 + row);
+        float2 v[32];  // d_model <= 1024: at most 32 tiles per group; all loads first, one round trip
+#pragma unroll
+        for (int t = 0; t < 32; ++t) v[t] = t < per ? sp[(size_t)t * a.m_stride] : float2{0.f, 0.f};
+        float sm = 0.f, m2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < 32; ++t) {
+            sm += v[t].x;  // entries beyond per are zero
+            m2 += v[t].y;
+        }
+        const float mean = sm / (float)per;
+        float dev = 0.f;
+#pragma unroll
+        for (int t = 0; t < 32; ++t)
+            if (t < per) dev += (v[t].x - mean) * (v[t].x - mean);
+        m2 += 16.f * dev;
+        row_stat[0][grp][row] = mean;
+        row_stat[1][grp][row] = m2;
+    }
     const int K = a.K, nk = K >> 6;
     const char* __restrict__ A = static_cast<const char*>(a.A);
     const char* __restrict__ W = static_cast<const char*>(a.W);
@@ -129,10 +156,29 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
     // epilogue: lane (r, g) of tile (i, j) holds C[m][n .. n+3], m = row r of the tile, n = 4 g
     const int r = lane & 15, g = lane >> 4;
     const T* __restrict__ bias = static_cast<const T*>(a.bias);
+    float rstd[WM], shift[WM];  // LNS: per row of this lane
+    if constexpr (LNS) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int rl = (wm * WM + i) * 16 + r;
+            const float a0 = row_stat[0][0][rl], a1 = row_stat[0][1][rl];
+            const float mu = 0.5f * (a0 + a1), d0 = a0 - mu, d1 = a1 - mu;
+            const float m2 = row_stat[1][0][rl] + row_stat[1][1][rl] + stat_n * (d0 * d0 + d1 * d1);
+            rstd[i] = 1.0f / sqrtf(m2 / (float)K + a.ln_eps);
+            shift[i] = m0 + rl < a.M ? mu - a.mu_hat_in[m0 + rl] : 0.f;
+            if (n0 == 0 && wn == 0 && g == 0 && m0 + rl < a.M) a.mu_hat_out[m0 + rl] = mu;  // for the next residual update
+        }
+    }
 #pragma unroll
     for (int j = 0; j < WN; ++j) {
         const int n = n0 + (wn * WN + j) * 16 + g * 4;
-        const f32x4 bv = bias ? load4(bias + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+        f32x4 bv, c1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (LNS) {
+            bv = *reinterpret_cast<const f32x4*>(a.ln_c2 + n);
+            c1 = *reinterpret_cast<const f32x4*>(a.ln_c1 + n);
+        } else {
+            bv = bias ? load4(bias + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             const int m = m0 + (wm * WM + i) * 16 + r;
@@ -140,25 +186,26 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
             f32x4 res = f32x4{0.f, 0.f, 0.f, 0.f};
             if constexpr (EPI == EPI_RESID)
                 res = *reinterpret_cast<const f32x4*>(static_cast<const char*>(a.out) + frag_elem_off<4>(m, n, a.N));
-            gemm_epilogue<T, EPI>(a, m, n, acc[i][j] + bv, res);
+            if constexpr (LNS) gemm_epilogue<T, EPI>(a, m, n, (acc[i][j] - shift[i] * c1) * rstd[i] + bv, res);
+            else gemm_epilogue<T, EPI>(a, m, n, acc[i][j] + bv, res);
         }
     }
 }
 
-template <int EPI, int WM, int WN, int D>
+template <int EPI, int WM, int WN, int D, bool LNS>
 static hipError_t launch_tiled_one(const GemmArgs& a, hipStream_t s) {
     constexpr int BM = 32 * WM, BN = 32 * WN;
     constexpr size_t kLds = 2ull * (BM / 16 + BN / 16) * 2048;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<EPI, WM, WN, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<EPI, WM, WN, D, LNS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
     const int grid = (tiles + 7) / 8 * 8;  // whole rounds over the 8 XCDs (surplus ids exit at once)
-    hipLaunchKernelGGL((gemm_tiled_kernel<EPI, WM, WN, D>), dim3(grid), dim3(256), kLds, s, a);
+    hipLaunchKernelGGL((gemm_tiled_kernel<EPI, WM, WN, D, LNS>), dim3(grid), dim3(256), kLds, s, a);
     return hipGetLastError();
 }
 
@@ -170,12 +217,23 @@ hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s) {
     //   128x128, D = 2: 410 / 419 (one workgroup per CU instead of two: registers)
     // Two co-resident workgroups matter more than tile size or prefetch depth: with 64x64 wavefront
     // tiles LDS reads alone need as many cycles as the MFMAs, so a second workgroup fills the gaps.
+    if (a.ln_c1) {  // LayerNorm folded around the product
+        if (!a.ln_c2 || !a.stats_in || !a.mu_hat_in || !a.mu_hat_out || a.stat_tiles < 2 || a.stat_tiles % 2 != 0 || a.stat_tiles > 64)
+            return hipErrorInvalidValue;
+        switch (epi) {
+            case EPI_QKV: return launch_tiled_one<EPI_QKV, 4, 4, 1, true>(a, s);
+            case EPI_F32: return launch_tiled_one<EPI_F32, 4, 4, 1, true>(a, s);
+            case EPI_RELU_T: return launch_tiled_one<EPI_RELU_T, 4, 4, 1, true>(a, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (epi) {
-        case EPI_CROSSKV: return launch_tiled_one<EPI_CROSSKV, 4, 4, 1>(a, s);
-        case EPI_QKV: return launch_tiled_one<EPI_QKV, 4, 4, 1>(a, s);
-        case EPI_RESID: return launch_tiled_one<EPI_RESID, 4, 4, 1>(a, s);
-        case EPI_F32: return launch_tiled_one<EPI_F32, 4, 4, 1>(a, s);
-        case EPI_RELU_T: return launch_tiled_one<EPI_RELU_T, 4, 4, 1>(a, s);
+        case EPI_CROSSKV: return launch_tiled_one<EPI_CROSSKV, 4, 4, 1, false>(a, s);
+        case EPI_QKV: return launch_tiled_one<EPI_QKV, 4, 4, 1, false>(a, s);
+        case EPI_RESID: return launch_tiled_one<EPI_RESID, 4, 4, 1, false>(a, s);
+        case EPI_F32: return launch_tiled_one<EPI_F32, 4, 4, 1, false>(a, s);
+        case EPI_RELU_T: return launch_tiled_one<EPI_RELU_T, 4, 4, 1, false>(a, s);
+        default: break;
     }
     return hipErrorInvalidValue;
 }

@@ -11,8 +11,15 @@ constexpr int kPage = 16;  // tokens per self-attention KV page
 
 // ---------------------------------------------------------------- decode GEMM
 // C[M,N] = prologue(A)[M,K] . W[N,K]^T (+bias), then an epilogue.
-enum GemmPro { PRO_LN = 0, PRO_T = 1 };
-enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROSSKV = 4 };
+// PRO_LNS (bfloat16 mode): the LayerNorm is folded around the product instead of being applied to the operand.
+// Whoever writes the residual rows x (embedding, EPI_RESID_S) also writes their "shadow" (x - mu_hat) * g in the
+// storage type and fragment order (mu_hat: the row mean before the update, so the shadow has no large common
+// offset; g: gain of the LayerNorm that reads it) and per-row statistics of x, and then
+//   W . LN(x) + bias = rstd * (W . shadow - (mu - mu_hat) * c1) + c2,  c1 = W . g,  c2 = W . b + bias,
+// so the product streams half the bytes of the float32 rows and needs no pass over them first.
+enum GemmPro { PRO_LN = 0, PRO_T = 1, PRO_LNS = 2 };
+// EPI_RESID_S: EPI_RESID that also writes the shadow and the statistics of the updated rows.
+enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROSSKV = 4, EPI_RESID_S = 5 };
 
 struct GemmArgs {
     const void* A;        // PRO_LN: float [M,K] (residual stream); PRO_T: T [M,K]; both in fragment order
@@ -39,6 +46,18 @@ struct GemmArgs {
     long long t_cap;
     const int* out_row_map;  // EPI_CROSSKV, may be null: frame slot that GEMM row m is written to (default m)
     int a_rows;              // rows the A buffer holds (0: only the next multiple of 128 above M is promised)
+    // Row statistics of the residual rows: for every row and every 16-column tile, the tile's mean and its sum
+    // of squared deviations from that mean, [stat_tiles][m_stride] (stat_tiles = d_model / 16).
+    const float2* stats_in;  // PRO_LNS: of A's rows
+    const float* mu_hat_in;  // PRO_LNS: [M] the shift the shadow was written with;
+                             // EPI_RESID_S: [M] row means before the update = the shift to write the shadow with
+    const float* ln_c1;      // PRO_LNS: [N]
+    const float* ln_c2;      // PRO_LNS: [N] (takes the place of bias)
+    float* mu_hat_out;       // PRO_LNS: [M] row means of A's rows, for the residual update that follows
+    float2* stats_out;       // EPI_RESID_S: of the updated rows
+    void* shadow_out;        // EPI_RESID_S: T [M,N] fragment order
+    const void* shadow_g;    // EPI_RESID_S: T [N]
+    int stat_tiles, m_stride;
 };
 
 // Buffers in fragment order must hold a multiple of 128 rows (rows >= M are read, never written).
@@ -51,6 +70,9 @@ hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s);
 // dst (fragment order [M,K]) <- rows of a row-major source; row m comes from src row row_map[m] (or m); K % 64 == 0
 hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, void* dst, int M, int K, hipStream_t s);
+// c1[n] = sum_k W[n,k] g[k], c2[n] = sum_k W[n,k] b[k] + bias[n] (float32 sums; W row-major [N,K], bias may be null)
+hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b, const void* bias, float* c1, float* c2,
+                          int N, int K, hipStream_t s);
 // dst (fragment order) <- src (row-major [N,K]); N % 16 == 0, K % 64 == 0
 hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s);
 
@@ -92,9 +114,18 @@ struct StateArgs {
     int prompt_len, prompt_stride, out_stride, max_new;
     int eos_id, pad_id, batch, vocab;
 };
-// x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]   (x in fragment order)
+// What the folded LayerNorm of the first layer needs beside the rows themselves (bfloat16 mode; see PRO_LNS).
+// shadow == null: not written.
+struct ShadowArgs {
+    void* shadow;       // T [B, d] fragment order: (x - row mean) * g
+    const void* g;      // T [d]: gain of the LayerNorm that reads the shadow
+    float2* stats;      // [d / 16][m_stride]: mean and sum of squared deviations of every 16-column tile
+    float* mu_hat;      // [B] row means (the shadow's shift)
+    int m_stride;
+};
+// x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]   (x in fragment order); d_model <= 1024
 hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,
-                        int d_model, int max_positions, float emb_scale, hipStream_t s);
+                        int d_model, int max_positions, float emb_scale, const ShadowArgs& sa, hipStream_t s);
 // greedy = 1: prompt feeding, argmax, EOS rules, output writes; greedy = 0: argmax only -> step_out (may be null)
 hipError_t launch_sample(const float* logits, const StateArgs& st, int greedy, int* step_out, hipStream_t s);
 // seq_len = n_gen = finished = 0, n_finished = 0, limit = limits ? limits[b] : INT_MAX, out_tokens = pad

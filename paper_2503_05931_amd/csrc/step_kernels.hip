@@ -15,35 +15,61 @@ namespace aed {
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(float* __restrict__ x, const T* __restrict__ tok_emb,
                                                     const T* __restrict__ pos_emb, StateArgs st, int d,
-                                                    int max_positions, float emb_scale) {
-    const int b = blockIdx.x;
+                                                    int max_positions, float emb_scale, ShadowArgs sh) {
+    const int b = blockIdx.x, tid = threadIdx.x;
     int tok = st.cur_tok[b];
     tok = tok < 0 ? 0 : (tok >= st.vocab ? st.vocab - 1 : tok);
     int pos = st.seq_len[b];
     pos = pos < max_positions ? pos : max_positions - 1;
     const T* e = tok_emb + (size_t)tok * d;
     const T* p = pos_emb + (size_t)pos * d;
-    for (int i = threadIdx.x * 4; i < d; i += 256 * 4) {
-        f32x4 ev = load4(e + i), pv = load4(p + i);
-        f32x4 o;
+    const int i = tid * 4;  // d <= 1024: one 4-vector per thread
+    const bool live = i < d;
+    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        const f32x4 ev = load4(e + i), pv = load4(p + i);
         o[0] = emb_scale * ev[0] + pv[0];
         o[1] = emb_scale * ev[1] + pv[1];
         o[2] = emb_scale * ev[2] + pv[2];
         o[3] = emb_scale * ev[3] + pv[3];
         store4(reinterpret_cast<float*>(reinterpret_cast<char*>(x) + frag_elem_off<4>(b, i, d)), o);
     }
+    if (!sh.shadow) return;
+    // row mean over the workgroup, then the shadow; tile statistics over the 4 threads of a 16-column tile
+    __shared__ float wsum[4];
+    float s = (o[0] + o[1]) + (o[2] + o[3]);
+    const float t4 = s;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    if ((tid & 63) == 0) wsum[tid >> 6] = s;
+    __syncthreads();
+    const float mean = (wsum[0] + wsum[1] + wsum[2] + wsum[3]) / (float)d;
+    float ts = t4;
+    ts += __shfl_xor(ts, 1);
+    ts += __shfl_xor(ts, 2);
+    const float tmean = ts * (1.f / 16.f);
+    float q = (o[0] - tmean) * (o[0] - tmean) + (o[1] - tmean) * (o[1] - tmean) + (o[2] - tmean) * (o[2] - tmean) +
+              (o[3] - tmean) * (o[3] - tmean);
+    q += __shfl_xor(q, 1);
+    q += __shfl_xor(q, 2);
+    if (!live) return;
+    const f32x4 gv = load4(static_cast<const T*>(sh.g) + i);
+    store4(reinterpret_cast<T*>(static_cast<char*>(sh.shadow) + frag_elem_off<sizeof(T)>(b, i, d)), (o - mean) * gv);
+    if ((tid & 3) == 0) sh.stats[(size_t)(i >> 4) * sh.m_stride + b] = float2{tmean, q};
+    if (tid == 0) sh.mu_hat[b] = mean;
 }
 
 hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,
-                        int d_model, int max_positions, float emb_scale, hipStream_t s) {
+                        int d_model, int max_positions, float emb_scale, const ShadowArgs& sa, hipStream_t s) {
+    if (d_model > 1024 || d_model % 64 != 0) return hipErrorInvalidValue;
     if (dt == kBF16)
         hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(st.batch), dim3(256), 0, s, x,
                            static_cast<const bf16_t*>(tok_emb), static_cast<const bf16_t*>(pos_emb), st, d_model,
-                           max_positions, emb_scale);
+                           max_positions, emb_scale, sa);
     else
         hipLaunchKernelGGL(embed_kernel<float>, dim3(st.batch), dim3(256), 0, s, x,
                            static_cast<const float*>(tok_emb), static_cast<const float*>(pos_emb), st, d_model,
-                           max_positions, emb_scale);
+                           max_positions, emb_scale, sa);
     return hipGetLastError();
 }
 
