@@ -369,10 +369,9 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Tile choice by a traffic model: a launch runs ceil(workgroups / 256) rounds on
-// the 256 CUs and each workgroup pulls (BM * bytes(A) + BN * bytes(W)) * K
-// through its CU; pick the candidate with the least bytes per CU, then the
-// fewest workgroups.
+// Tile choice by a traffic model: each workgroup pulls (BM * bytes(A) + BN * bytes(W)) * K
+// through its CU and the launch's workgroups are spread over the 256 CUs; pick the
+// candidate with the least bytes per CU, then the fewest workgroups.
 template <typename T, int PRO, int EPI>
 static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
     struct Cand { int mt, nt; };
@@ -388,7 +387,12 @@ static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
         const int bm = 16 * cands[c].mt, bn = 16 * cands[c].nt;
         if (a.N % bn != 0) continue;
         const long wgs = (long)((a.M + bm - 1) / bm) * (a.N / bn);
-        const double cost = (double)((wgs + 255) / 256) * (bm * a_bytes + bn * w_bytes);
+        // Workgroups of the smaller tiles share a CU (two or three fit by registers), so beyond 256 workgroups the
+        // bytes through a CU grow in proportion, not in whole rounds.  The 64 x 64 tile runs one workgroup per CU
+        // and its long serial stream costs about half more than its bytes say (measured at M = 256:
+        // 9.7 us against 8.2 us for the 32 x 64 tile on the QKV product).
+        const double rounds = wgs > 256 ? (double)wgs / 256.0 : 1.0;
+        const double cost = rounds * (bm * a_bytes + bn * w_bytes) * (c == 4 ? 1.6 : 1.0);
         if (cost < best_cost || (cost == best_cost && wgs < best_wgs)) { best = c; best_cost = cost; best_wgs = wgs; }
     }
     if (best == 0) return launch_one<T, PRO, EPI, 1, 1>(a, s);
@@ -405,7 +409,7 @@ constexpr int kLnFusedMaxM = 128;
 // The LDS-tiled kernel (bf16, 128 x 128 tiles) takes over once its tiles fill the GPU; below that
 // the streaming kernel's 256+ small workgroups are faster (measured at M = 1024: N = 1024 gives 64
 // tiles and 17.8 us against 7.6 us streamed; N = 4096 gives 256 tiles and 23.8 us against 28.4 us).
-constexpr int kTiledMinTiles = 256;
+constexpr int kTiledMinTiles = 160;
 template <typename T> static bool use_tiled(const GemmArgs& a) {
     return sizeof(T) == 2 && a.N % 128 == 0 && (long)((a.M + 127) / 128) * (a.N / 128) >= kTiledMinTiles;
 }
