@@ -266,6 +266,27 @@ def test_direct_to_lds_cross_kv_precompute(torch_cuda, oracle, d_model, n_heads,
     dec.close()
 
 
+def test_folded_layernorm_with_a_large_row_mean(torch_cuda, oracle):
+    """bf16 mode rounds (x - mu_hat) * g, not LN(x), to bf16 (the LayerNorm is folded around the products), which
+    is only as accurate if mu_hat stays close to the row mean.  Rows with a common offset of 8 standard deviations
+    (embeddings shifted by a constant) would cost 8x the rounding error with mu_hat = 0; with the previous update's
+    mean as mu_hat the logits must stay inside the usual tolerance."""
+    from tests import gpu_util as G
+    wl = unit_workload("bf16", 512, 4, 128, [40, 7, 130, 64, 1, 99], seed=57, n_layers=3, d_ffn=1024, vocab=256, max_new=12)
+    w = wl.weights
+    scale = float(wl.cfg.emb_scale)
+    sd = float(np.std(scale * w["tok_emb"]))
+    w["pos_emb"] = W.bf16_round((w["pos_emb"] + 8.0 * sd).astype(np.float32))
+    m = oracle.Model(wl.cfg, w)
+    toks = random_tokens(wl.cfg, 6, 10, 58)
+    ref = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
+    print(f"rows with mean = 8 sigma: max |dlogit| = {err:.2e}, near ties {near}")
+    dec.close()
+
+
 def test_degenerate_shapes_and_reuse(torch_cuda, oracle):
     """Batch of one, one-token prompt, one new token, a decode length that ends exactly on a page boundary,
     EOS as the very first token, repeated greedy calls of different lengths on one batch (the launch graph is
