@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaed.so")
-SOURCES = ("aed_api.hip", "gemm_decode.hip", "gemm_tiled.hip", "gemm_dma.hip", "attn_decode.hip", "step_kernels.hip")
+SOURCES = ("aed_api.hip", "gemm_decode.hip", "gemm_tiled.hip", "gemm_dma.hip", "gemm_dma128.hip", "attn_decode.hip", "step_kernels.hip")
 HOST_SOURCES = ("batching.cpp",)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -212,6 +212,8 @@ static hipError_t launch_tiled_one(const GemmArgs& a, hipStream_t s) {
 // bf16 only; A (fragment order) padded to a multiple of 128 rows in memory; N % 128 == 0; K % 64 == 0.
 hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s) {
     if (a.M < 1 || a.N % 128 != 0 || a.K % 64 != 0) return hipErrorInvalidValue;
+    // from 8 k-blocks on, the same tile fed by direct-to-LDS loads (several k-steps in flight) is used instead
+    if (a.K >= 512 && epi != EPI_RESID) return launch_gemm_dma128(epi, a, s);
     // Measured on MI355X for the cross K/V GEMM (K = 1024, N = 2048, bf16), TFLOP/s at M = 7 217 / 512 000:
     //   128x128 tile, D = 1: 627 / 684      256x128, D = 1: 485 / 529      128x64, D = 1: 567 / 621
     //   128x128, D = 2: 410 / 419 (one workgroup per CU instead of two: registers)

@@ -66,6 +66,8 @@ struct GemmArgs {
 hipError_t launch_gemm(Dtype dt, GemmPro pro, GemmEpi epi, const GemmArgs& a, hipStream_t s);
 // LDS-tiled MFMA GEMM for large M (bf16 only; fragment-order A padded to a multiple of 128 rows, N % 128 == 0)
 hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s);
+// the same 128 x 128 tile fed by direct-to-LDS loads (bf16, K >= 512, not EPI_RESID); a.ln_c1 != null: PRO_LNS
+hipError_t launch_gemm_dma128(GemmEpi epi, const GemmArgs& a, hipStream_t s);
 // bf16 cross K/V product with 256 x 256 tiles fed by direct-to-LDS loads; A must hold whole 256-row tiles
 hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s);
 // dst (fragment order [M,K]) <- rows of a row-major source; row m comes from src row row_map[m] (or m); K % 64 == 0
