@@ -39,7 +39,7 @@ def measured_traffic(kernel, workload):
         return None
 
 
-def run_workload(name, steps, warmup, want_roofline, eager=False):
+def run_workload(name, steps, warmup, want_roofline, eager=False, no_prefill=False):
     import numpy as np
     import torch
     from paper_2503_05931_amd import binding, workloads as W
@@ -49,8 +49,10 @@ def run_workload(name, steps, warmup, want_roofline, eager=False):
     B = cfg.batch
     # eager: the library is given the default (NULL) stream, on which it launches every kernel directly
     # instead of replaying a captured graph (used for hardware-counter runs)
+    # the prompt positions before the last go through the layers in one pass (rows: 16-aligned batch per position)
+    prefill_rows = 0 if no_prefill else min(cfg.prompt_len - 1, 8) * ((B + 15) // 16 * 16)
     dec = binding.Decoder(cfg, wl.weights, max_batch=B, max_total_enc_frames=int(wl.enc_lens.sum()),
-                          max_dec_len=cfg.max_dec_len,
+                          max_dec_len=cfg.max_dec_len, prefill_rows=prefill_rows,
                           stream=torch.cuda.default_stream(torch.device("cuda:0")) if eager else None)
     enc = dec.to_device(wl.enc)
     prompt = torch.from_numpy(wl.prompt).to(dec.device)
@@ -89,7 +91,8 @@ def run_workload(name, steps, warmup, want_roofline, eager=False):
     torch.cuda.synchronize()
     d2 = time.perf_counter() - t0
     res["decode_only_tokens_per_s"] = tokens / d2
-    res["decode_ms_per_token_step"] = 1e3 * d2 / (cfg.prompt_len - 1 + cfg.max_new)
+    # decoder steps of the loop: without prefill the prompt positions before the last are steps too
+    res["decode_ms_per_token_step"] = 1e3 * d2 / ((cfg.prompt_len - 1 if no_prefill else 0) + cfg.max_new)
     if wl.durations_s is not None:
         res["decoder_rtfx"] = float(np.sum(wl.durations_s)) * steps / dt
 
@@ -231,6 +234,8 @@ def main():
     ap.add_argument("--workload", default="canary24_b64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="skip the 4-layer decoder's extra line")
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="feed the prompt one position per decoder step instead of prefilling it in one pass")
     ap.add_argument("--eager", action="store_true",
                     help="launch kernels directly on the default stream instead of replaying the captured graph")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -265,7 +270,8 @@ def main():
         dst.copy_(src)   # one copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    res, wl = run_workload(args.workload, args.steps, args.warmup, want_roofline=True, eager=args.eager)
+    res, wl = run_workload(args.workload, args.steps, args.warmup, want_roofline=True, eager=args.eager,
+                           no_prefill=args.no_prefill)
     cfg = wl.cfg
     line = {
         "metric": "decoded tokens/sec at 1 MI355X (24L and 4L decoder) + % HBM/MFMA roofline",
@@ -284,7 +290,8 @@ def main():
                    "batch": cfg.batch, "prompt_len": cfg.prompt_len, "max_new": cfg.max_new,
                    "enc_frames_total": int(wl.enc_lens.sum()),
                    "step": "cross K/V precompute + greedy decode of the batch",
-                   "launch": "eager" if args.eager else "graph"},
+                   "launch": "eager" if args.eager else "graph",
+                   "prompt": "token by token" if args.no_prefill else "positions before the last in one pass"},
         "decode_only_tokens_per_s": res["decode_only_tokens_per_s"],
         "decode_ms_per_token_step": res["decode_ms_per_token_step"],
         "precompute_ms": res["precompute_ms"],
@@ -294,7 +301,7 @@ def main():
         "mfma_roofline": res.get("mfma"),
     }
     if not args.no_also and args.workload == "canary24_b64":
-        r4, _ = run_workload("flash4_b256", args.steps, args.warmup, want_roofline=False)
+        r4, _ = run_workload("flash4_b256", args.steps, args.warmup, want_roofline=False, no_prefill=args.no_prefill)
         line["also"] = [{"workload": "flash4_b256", "n_layers": 4, "batch": 256, "value": r4["tokens_per_s"],
                          "unit": "tokens/s", "ms_per_step": r4["ms_per_step"],
                          "decode_only_tokens_per_s": r4["decode_only_tokens_per_s"],

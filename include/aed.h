@@ -69,6 +69,7 @@ typedef struct aed_config {
     int32_t eos_id;        /* < 0: never stop on EOS */
     int32_t pad_id;        /* written to out_tokens after a sequence has finished */
     float ln_eps, emb_scale;
+    int32_t prefill_rows;  /* capacity: rows of one prompt-prefill pass (see aed_greedy_decode); 0 = none */
 } aed_config;
 
 /* DEVICE pointers, element type per aed_config.dtype. */

@@ -36,7 +36,7 @@ class AedConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_int32) for n in (
         "n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "max_positions", "dtype", "norm_type",
         "page_size", "max_batch", "max_total_enc_frames", "max_dec_len", "kv_pages", "eos_id", "pad_id")] + [
-        ("ln_eps", C.c_float), ("emb_scale", C.c_float)]
+        ("ln_eps", C.c_float), ("emb_scale", C.c_float), ("prefill_rows", C.c_int32)]
 
 
 class AedLayerWeights(C.Structure):
@@ -89,7 +89,8 @@ def load():
     return lib
 
 
-def make_config(cfg, max_batch: int, max_total_enc_frames: int, max_dec_len: int, kv_pages: int = 0) -> AedConfig:
+def make_config(cfg, max_batch: int, max_total_enc_frames: int, max_dec_len: int, kv_pages: int = 0,
+                prefill_rows: int = 0) -> AedConfig:
     c = AedConfig()
     c.struct_size = C.sizeof(AedConfig)
     for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "max_positions", "norm_type",
@@ -99,6 +100,7 @@ def make_config(cfg, max_batch: int, max_total_enc_frames: int, max_dec_len: int
     c.max_batch, c.max_total_enc_frames, c.max_dec_len, c.kv_pages = (int(max_batch), int(max_total_enc_frames),
                                                                       int(max_dec_len), int(kv_pages))
     c.ln_eps, c.emb_scale = float(cfg.ln_eps), float(cfg.emb_scale)
+    c.prefill_rows = int(prefill_rows)
     return c
 
 
@@ -127,7 +129,8 @@ class Decoder:
     device, workspace).  Methods carry the C entry points' names."""
 
     def __init__(self, cfg, weights: Dict, max_batch: int, max_total_enc_frames: int, max_dec_len: int,
-                 device: str = "cuda:0", stream=None, kv_pages: int = 0, workspace_fill: Optional[int] = None):
+                 device: str = "cuda:0", stream=None, kv_pages: int = 0, workspace_fill: Optional[int] = None,
+                 prefill_rows: int = 0):
         """workspace_fill: byte value written over the whole workspace before the decoder is
         created (0xFF makes every untouched bf16/fp32 slot read as NaN), for leak checks."""
         import torch
@@ -135,7 +138,7 @@ class Decoder:
         self.cfg = cfg
         self.device = torch.device(device)
         self.lib = load()
-        self.c_cfg = make_config(cfg, max_batch, max_total_enc_frames, max_dec_len, kv_pages)
+        self.c_cfg = make_config(cfg, max_batch, max_total_enc_frames, max_dec_len, kv_pages, prefill_rows)
         self.tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
         self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
         self._keep = []

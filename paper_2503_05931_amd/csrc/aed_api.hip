@@ -22,6 +22,7 @@ namespace {
 constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
 constexpr int kTargetItems = 512;      // work items aimed at per attention launch when sequences are cut
 constexpr int kMinItemsNoSplit = 128;  // batch * heads from which sequences are never cut
+constexpr int kMaxPrefillPositions = 8;  // prompt positions per prefill pass
 
 thread_local std::string g_create_error;
 
@@ -33,6 +34,8 @@ struct Layout {
     size_t stats_elems;  // float2 per statistics buffer
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished, step_tok;
     size_t prompt_buf, out_buf, page_table, enc_off, row_map, frame_map, turn_buf, items, part, counters;
+    size_t v_seq_len, v_finished, v_cur_tok, v_page_table, v_items;  // state of a prompt-prefill pass's rows
+    int act_rows;  // rows the activation buffers hold: max(max_batch, prefill_rows)
     size_t k_pool, v_pool, kc, vc, w_frag, enc_frag;
     size_t total;
     int max_pages, n_pages, max_items;
@@ -61,13 +64,17 @@ aed_status check_config(const aed_config* c, std::string& err) {
     if (c->d_ffn % 256 != 0) return unsup("d_ffn must be a multiple of 256");
     if (c->vocab % 64 != 0) return unsup("vocab must be a multiple of 64");
     if (c->max_batch > 65535) return unsup("max_batch above 65535");
+    if (c->prefill_rows < 0 || c->prefill_rows > 65535) return bad("prefill_rows must be in [0, 65535]");
     return AED_OK;
 }
 
 void make_layout(const aed_config* c, Layout* L) {
     const size_t e = c->dtype == 1 ? 2 : 4;
     const size_t B = c->max_batch, d = c->d_model, H = c->n_heads, Dh = c->head_dim;
-    const size_t Bp = align_up(B, 128);  // fragment-order activations are read in whole tiles of up to 128 rows
+    // activations hold the rows of a decode step or of a prompt-prefill pass, whichever is more
+    const size_t Ba = std::max<size_t>(B, (size_t)c->prefill_rows);
+    L->act_rows = (int)Ba;
+    const size_t Bp = align_up(Ba, 128);  // fragment-order activations are read in whole tiles of up to 128 rows
     L->max_pages = (c->max_dec_len + kPage - 1) / kPage;
     L->n_pages = c->kv_pages > 0 ? c->kv_pages : (int)(B * L->max_pages);
     L->max_items = c->max_total_enc_frames / 64 + c->max_batch;
@@ -76,7 +83,7 @@ void make_layout(const aed_config* c, Layout* L) {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L->x = take(Bp * d * 4);
-    L->q = take(B * d * 4);
+    L->q = take(Ba * d * 4);
     L->logits = take(B * (size_t)c->vocab * 4);
     L->attn_out = take(Bp * d * e);
     L->ffn_h = take(Bp * (size_t)c->d_ffn * e);
@@ -104,8 +111,13 @@ void make_layout(const aed_config* c, Layout* L) {
     L->frame_map = take((size_t)c->max_total_enc_frames * 4);  // request queue: where each new frame's K/V goes
     L->turn_buf = take(B * 4 * 4);                            // request queue: slot, old / new request, limit
     L->items = take((size_t)L->max_items * 16);
-    L->part = take(B * H * kMaxChunks * (Dh + 2) * 4);
-    L->counters = take(B * H * 4);
+    L->part = take(Ba * H * kMaxChunks * (Dh + 2) * 4);
+    L->counters = take(Ba * H * 4);
+    L->v_seq_len = take(Ba * 4);
+    L->v_finished = take(Ba * 4);
+    L->v_cur_tok = take(Ba * 4);
+    L->v_page_table = take(c->prefill_rows > 0 ? Ba * (size_t)L->max_pages * 4 : 0);
+    L->v_items = take(c->prefill_rows > 0 ? (size_t)L->max_items * kMaxPrefillPositions * 16 : 0);
     L->k_pool = take(L->pool_layer_elems * c->n_layers * e);
     L->v_pool = take(L->pool_layer_elems * c->n_layers * e);
     L->kc = take(L->cross_layer_elems * c->n_layers * e);
@@ -156,6 +168,7 @@ struct aed_decoder {
     const void* last_enc = nullptr;
     bool last_enc_padded = false;
     std::vector<int> enc_lens, enc_off, page_table;
+    std::vector<int4> items_host;  // the cross-attention work list of the batch (a prefill pass repeats it per position)
     int* pin_poll = nullptr;  // pinned host memory for the finished-count poll
     hipEvent_t poll_event[2] = {nullptr, nullptr};
     hipEvent_t t0 = nullptr, t1 = nullptr;
@@ -163,6 +176,8 @@ struct aed_decoder {
     GraphKey gkey;
     hipGraphExec_t step_gexec = nullptr;  // one aed_decode_step step (argmax only, ids into step_tok)
     GraphKey step_gkey;
+    hipGraphExec_t pf_gexec = nullptr;    // one prompt-prefill pass
+    GraphKey pf_gkey;
     std::string err;
 
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -496,6 +511,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     }
     d->batch = batch;
     d->n_items = (int)items.size();
+    d->items_host = items;
     d->cross_chunk = chunk;
     d->total_enc = total;
     d->last_enc = enc;
@@ -510,7 +526,7 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     d->state = aed_decoder::NO_BATCH;
 
     StateArgs st = d->state_args(0, 0);
-    HIP_TRY(d, launch_reset(st, nullptr, 0, d->stream));
+    HIP_TRY(d, launch_reset(st, nullptr, 0, 0, d->stream));
     // encoder frames -> fragment order once (gathering the valid rows of a padded tensor), then one GEMM per layer
     HIP_TRY(d, launch_reorder_rows(d->dt, enc, padded ? d->at<int>(d->lay.row_map) : nullptr, d->ws + d->lay.enc_frag,
                                    (int)total, d->cfg.d_model, d->stream));
@@ -520,14 +536,14 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
     return AED_OK;
 }
 
-// Capture one step (greedy or plain) into a launch graph; an existing graph of the same shape is kept.
-aed_status ensure_graph(aed_decoder* d, const StateArgs& st, int greedy, int* step_out, const GraphKey& key,
-                        hipGraphExec_t* exec, GraphKey* have) {
+// Capture what enqueue launches into a launch graph; an existing graph of the same shape is kept.
+template <typename F>
+aed_status ensure_graph_of(aed_decoder* d, F enqueue, const GraphKey& key, hipGraphExec_t* exec, GraphKey* have) {
     if (*exec && key == *have) return AED_OK;
     if (*exec) { (void)hipGraphExecDestroy(*exec); *exec = nullptr; }
     hipGraph_t graph = nullptr;
     HIP_TRY(d, hipStreamBeginCapture(d->stream, hipStreamCaptureModeThreadLocal));
-    hipError_t e = enqueue_step(d, st, greedy, step_out);
+    hipError_t e = enqueue();
     hipError_t e2 = hipStreamEndCapture(d->stream, &graph);
     if (e != hipSuccess || e2 != hipSuccess) {
         if (graph) (void)hipGraphDestroy(graph);
@@ -539,10 +555,99 @@ aed_status ensure_graph(aed_decoder* d, const StateArgs& st, int greedy, int* st
     *have = key;
     return AED_OK;
 }
+// one step (greedy or plain)
+aed_status ensure_graph(aed_decoder* d, const StateArgs& st, int greedy, int* step_out, const GraphKey& key,
+                        hipGraphExec_t* exec, GraphKey* have) {
+    return ensure_graph_of(d, [&]() { return enqueue_step(d, st, greedy, step_out); }, key, exec, have);
+}
 
 aed_status upload_page_table(aed_decoder* d) {
     HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.page_table), d->page_table.data(), d->page_table.size() * 4,
                               hipMemcpyHostToDevice, d->stream));
+    return AED_OK;
+}
+
+// Prompt positions [p0, p1) of every sequence through the layers in one pass (greedy decoding only; see aed.h).
+// Row r = (p - p0) * Bs + b (Bs = batch rounded up to 16, padding rows marked finished) is a sequence of its own
+// for the kernels: position p, token prompt[b][p], sequence b's pages and encoder frames.  Only the self-attention
+// keys and values matter afterwards, so the last layer stops after its QKV product.
+aed_status prefill_pass(aed_decoder* d, const std::vector<int>& prompt_host, int prompt_len, int p0, int p1) {
+    const int B = d->batch, Bs = (B + 15) / 16 * 16, np = p1 - p0, R = np * Bs, MP = d->lay.max_pages;
+    std::vector<int> seq(R), fin(R), tok(R), pt((size_t)R * MP);
+    std::vector<int4> items;
+    items.reserve(d->items_host.size() * np);
+    for (int q = 0; q < np; ++q) {
+        for (int b = 0; b < Bs; ++b) {
+            const int r = q * Bs + b;
+            seq[r] = p0 + q;
+            fin[r] = b >= B;
+            tok[r] = b < B ? prompt_host[(size_t)b * prompt_len + p0 + q] : 0;
+            for (int k = 0; k < MP; ++k) pt[(size_t)r * MP + k] = b < B ? d->page_table[(size_t)b * MP + k] : 0;
+        }
+    }
+    for (const int4& it : d->items_host)  // longest first stays longest first
+        for (int q = 0; q < np; ++q) {
+            int4 v = it;
+            v.x = q * Bs + it.x;
+            items.push_back(v);
+        }
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.v_seq_len), seq.data(), seq.size() * 4, hipMemcpyHostToDevice, d->stream));
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.v_finished), fin.data(), fin.size() * 4, hipMemcpyHostToDevice, d->stream));
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.v_cur_tok), tok.data(), tok.size() * 4, hipMemcpyHostToDevice, d->stream));
+    HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.v_page_table), pt.data(), pt.size() * 4, hipMemcpyHostToDevice, d->stream));
+    HIP_TRY(d, hipMemcpyAsync(d->at<int4>(d->lay.v_items), items.data(), items.size() * 16, hipMemcpyHostToDevice, d->stream));
+    // the kernels find their state through the layout: point it at the pass's rows for the duration
+    const Layout saved = d->lay;
+    const int saved_batch = d->batch, saved_items = d->n_items, saved_chunk = d->self_chunk, saved_nch = d->self_nchunks;
+    d->lay.seq_len = saved.v_seq_len;
+    d->lay.finished = saved.v_finished;
+    d->lay.cur_tok = saved.v_cur_tok;
+    d->lay.page_table = saved.v_page_table;
+    d->lay.items = saved.v_items;
+    d->batch = R;
+    d->n_items = (int)items.size();
+    d->self_chunk = std::max(64, (p1 + 63) / 64 * 64);  // a position sees at most p1 keys: one work item each
+    d->self_nchunks = 1;
+    const StateArgs st = d->state_args(0, 0);
+    auto enqueue = [&]() -> hipError_t {
+        ShadowArgs sa;
+        memset(&sa, 0, sizeof sa);
+        if (folded_ln(d)) {
+            d->x_par = 0;
+            sa.shadow = d->ws + d->lay.x_shadow;
+            sa.g = d->layers[0].ln1_g;
+            sa.stats = stats_buf(d, 0);
+            sa.mu_hat = shift_buf(d, 1);
+            sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+        }
+        hipError_t e = launch_embed(d->dt, d->at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
+                                    d->cfg.max_positions, d->cfg.emb_scale, sa, d->stream);
+        for (int l = 0; l < d->cfg.n_layers && e == hipSuccess; ++l) {
+            const int last_cls = l + 1 < d->cfg.n_layers ? AED_K_FFN2 : AED_K_LN_QKV;
+            for (int cls = AED_K_LN_QKV; cls <= last_cls && e == hipSuccess; ++cls) e = k_class(d, cls, l);
+        }
+        return e;
+    };
+    // the pass's launches depend on its shape only (the tables above are read on the device): one graph per shape
+    aed_status grc = AED_OK;
+    hipError_t e = hipSuccess;
+    if (d->stream != nullptr) {
+        GraphKey key;
+        key.batch = R; key.n_items = d->n_items; key.self_chunk = d->self_chunk; key.self_nchunks = 1;
+        key.total_enc = d->total_enc;
+        grc = ensure_graph_of(d, enqueue, key, &d->pf_gexec, &d->pf_gkey);
+        if (grc == AED_OK) e = hipGraphLaunch(d->pf_gexec, d->stream);
+    } else {
+        e = enqueue();
+    }
+    d->lay = saved;
+    d->batch = saved_batch;
+    d->n_items = saved_items;
+    d->self_chunk = saved_chunk;
+    d->self_nchunks = saved_nch;
+    if (grc != AED_OK) return grc;
+    if (e != hipSuccess) return fail(d, AED_EHIP, "prompt prefill: %s", hipGetErrorString(e));
+    HIP_TRY(d, hipStreamSynchronize(d->stream));  // the host tables above go out of scope
     return AED_OK;
 }
 
@@ -605,7 +710,7 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
     if ((e = hipEventCreate(&d->t1)) != hipSuccess) return cleanup(e, "hipEventCreate");
 
     // arrival counters of the chunk merge start at zero and return to zero after every launch
-    if ((e = hipMemsetAsync(d->ws + L.counters, 0, (size_t)cfg->max_batch * cfg->n_heads * 4, d->stream)) != hipSuccess)
+    if ((e = hipMemsetAsync(d->ws + L.counters, 0, (size_t)L.act_rows * cfg->n_heads * 4, d->stream)) != hipSuccess)
         return cleanup(e, "hipMemsetAsync");
     // re-order every weight matrix into fragment order, once
     {
@@ -664,6 +769,7 @@ aed_status aed_decoder_destroy(aed_decoder* d) {
     (void)hipStreamSynchronize(d->stream);
     if (d->gexec) (void)hipGraphExecDestroy(d->gexec);
     if (d->step_gexec) (void)hipGraphExecDestroy(d->step_gexec);
+    if (d->pf_gexec) (void)hipGraphExecDestroy(d->pf_gexec);
     for (int i = 0; i < 2; ++i)
         if (d->poll_event[i]) (void)hipEventDestroy(d->poll_event[i]);
     if (d->t0) (void)hipEventDestroy(d->t0);
@@ -771,7 +877,24 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
     d->last_prompt_len = prompt_len;
     d->last_max_new = max_new;
     StateArgs st = d->state_args(prompt_len, max_new);
-    HIP_TRY(d, launch_reset(st, max_new_per_seq ? d->at<int>(d->lay.limits_in) : nullptr, 1, d->stream));
+    // Prompt positions 0 .. prompt_len-2 emit nothing: with room for it they go through the layers several at a
+    // time; the step loop then starts at the last prompt position.
+    int start_pos = 0;
+    {
+        const int Bs = (B + 15) / 16 * 16;
+        const int per_pass = std::min(kMaxPrefillPositions, d->cfg.prefill_rows / Bs);
+        if (per_pass >= 1 && prompt_len >= 2) {
+            std::vector<int> prompt_host((size_t)B * prompt_len);
+            HIP_TRY(d, hipMemcpyAsync(prompt_host.data(), prompt, prompt_host.size() * 4, hipMemcpyDeviceToHost, d->stream));
+            HIP_TRY(d, hipStreamSynchronize(d->stream));
+            while (start_pos < prompt_len - 1) {
+                const int p1 = std::min(prompt_len - 1, start_pos + per_pass);
+                if ((rc = prefill_pass(d, prompt_host, prompt_len, start_pos, p1)) != AED_OK) return rc;
+                start_pos = p1;
+            }
+        }
+    }
+    HIP_TRY(d, launch_reset(st, max_new_per_seq ? d->at<int>(d->lay.limits_in) : nullptr, 1, start_pos, d->stream));
     d->state = aed_decoder::CONSUMED;
 
     // one launch graph per shape; replayed for every step
@@ -786,7 +909,7 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
     // Early stop: every poll_every steps the finished count is copied to pinned
     // memory; completed polls are read without blocking, and the host runs at
     // most two polls ahead of the device.
-    const int n_steps = prompt_len - 1 + max_new;
+    const int n_steps = prompt_len - 1 - start_pos + max_new;
     const bool can_stop_early = d->cfg.eos_id >= 0;
     const int poll_every = 8;
     int issued = 0, seen = 0;

@@ -270,7 +270,7 @@ hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s) {
-    if (a.chunk < 64 || a.chunk % 64 != 0 || !a.items || a.n_items < a.batch) return hipErrorInvalidValue;
+    if (a.chunk < 64 || a.chunk % 64 != 0 || !a.items || a.n_items < 1) return hipErrorInvalidValue;
     dim3 grid(a.n_heads, a.n_items);
     return dt == kBF16 ? launch_dh<bf16_t, false>(a, grid, s) : launch_dh<float, false>(a, grid, s);
 }

@@ -130,8 +130,9 @@ hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos
                         int d_model, int max_positions, float emb_scale, const ShadowArgs& sa, hipStream_t s);
 // greedy = 1: prompt feeding, argmax, EOS rules, output writes; greedy = 0: argmax only -> step_out (may be null)
 hipError_t launch_sample(const float* logits, const StateArgs& st, int greedy, int* step_out, hipStream_t s);
-// seq_len = n_gen = finished = 0, n_finished = 0, limit = limits ? limits[b] : INT_MAX, out_tokens = pad
-hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out, hipStream_t s);
+// seq_len = start_pos, cur_tok = prompt[b][start_pos], n_gen = finished = 0, n_finished = 0,
+// limit = limits ? limits[b] : INT_MAX, out_tokens = pad (fill_out)
+hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out, int start_pos, hipStream_t s);
 // cur_tok[b] = src[b * stride]
 hipError_t launch_set_tokens(int* cur_tok, const int* src, int stride, int batch, hipStream_t s);
 // out[b] = n_gen[b]; dst[b, t] = out_tokens[b, t]

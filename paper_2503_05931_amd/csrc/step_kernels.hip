@@ -133,13 +133,13 @@ hipError_t launch_sample(const float* logits, const StateArgs& st, int greedy, i
     return hipGetLastError();
 }
 
-__global__ void reset_kernel(StateArgs st, const int* __restrict__ limits, int fill_out) {
+__global__ void reset_kernel(StateArgs st, const int* __restrict__ limits, int fill_out, int start_pos) {
     const int b = blockIdx.x;
     if (threadIdx.x == 0) {
-        st.seq_len[b] = 0;
+        st.seq_len[b] = start_pos;
         st.n_gen[b] = 0;
         st.finished[b] = 0;
-        st.cur_tok[b] = st.prompt ? st.prompt[(size_t)b * st.prompt_stride] : 0;
+        st.cur_tok[b] = st.prompt ? st.prompt[(size_t)b * st.prompt_stride + start_pos] : 0;
         st.limit[b] = limits ? limits[b] : INT_MAX;
         if (b == 0) *st.n_finished = 0;
     }
@@ -147,8 +147,8 @@ __global__ void reset_kernel(StateArgs st, const int* __restrict__ limits, int f
         for (int t = threadIdx.x; t < st.max_new; t += blockDim.x) st.out_tokens[(size_t)b * st.out_stride + t] = st.pad_id;
 }
 
-hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out, hipStream_t s) {
-    hipLaunchKernelGGL(reset_kernel, dim3(st.batch), dim3(64), 0, s, st, limits_dev, fill_out);
+hipError_t launch_reset(const StateArgs& st, const int* limits_dev, int fill_out, int start_pos, hipStream_t s) {
+    hipLaunchKernelGGL(reset_kernel, dim3(st.batch), dim3(64), 0, s, st, limits_dev, fill_out, start_pos);
     return hipGetLastError();
 }
 

@@ -8,13 +8,13 @@ from paper_2503_05931_amd import binding, workloads as W
 TOL = {"fp32": 1e-4, "bf16": 3e-2}
 
 
-def make_decoder(wl, max_batch=None, max_total=None, max_dec_len=None, poison=True, kv_pages=0):
+def make_decoder(wl, max_batch=None, max_total=None, max_dec_len=None, poison=True, kv_pages=0, prefill_rows=0):
     cfg = wl.cfg
     B = len(wl.enc_lens)
     dec = binding.Decoder(cfg, wl.weights,
                           max_batch=max_batch or B,
                           max_total_enc_frames=max_total or int(wl.enc_lens.sum()),
-                          max_dec_len=max_dec_len or cfg.max_dec_len, kv_pages=kv_pages,
+                          max_dec_len=max_dec_len or cfg.max_dec_len, kv_pages=kv_pages, prefill_rows=prefill_rows,
                           # every byte the library has not written itself reads as NaN, so a read of an
                           # unwritten cache slot or of padding shows up in the logits
                           workspace_fill=0xFF if poison else None)

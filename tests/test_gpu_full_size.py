@@ -46,6 +46,20 @@ def test_canary24_b64_sampled_sequences(oracle):
     assert (gids[others][:, P - 1:] == toks[others]).all()
     dec.close()
 
+    # the configuration bench.py times: the prompt positions before the last prefilled in one pass
+    B = len(wl.enc_lens)
+    dec = G.make_decoder(wl, poison=True, prefill_rows=(P - 1) * ((B + 15) // 16 * 16))
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    toks_p, lens_p = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), cfg.max_new)
+    toks_p, lens_p = toks_p.cpu().numpy(), lens_p.cpu().numpy()
+    assert (lens_p == cfg.max_new).all()
+    for i, b in enumerate(SAMPLE):
+        assert (toks_p[b, :first[i]] == ref_toks[i, :first[i]]).all(), f"with prefill: sequence {b} forks before a near tie"
+    same = int((toks_p == toks).all(axis=1).sum())
+    print(f"with prompt prefill: {same} of {B} sequences token-identical to the run without it "
+          "(the prompt's keys and values come from products of a different shape; forks start at near-ties)")
+    dec.close()
+
 
 def _forced_check(oracle, wl, sample, n_new, tol, max_dec_len=None):
     """Greedy-decode the oracle on the sampled sequences for n_new tokens, then run the whole batch through

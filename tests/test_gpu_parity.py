@@ -287,6 +287,43 @@ def test_folded_layernorm_with_a_large_row_mean(torch_cuda, oracle):
     dec.close()
 
 
+@pytest.mark.parametrize("dtype,prompt_len,prefill_rows", [
+    ("fp32", 6, 16 * 8),     # all five positions before the last in one pass (batch 5 -> 16 rows per position)
+    ("fp32", 6, 16 * 2),     # two positions per pass: three passes
+    ("bf16", 11, 16 * 4),    # bf16 (LayerNorm folded around the products), ten positions in passes of four
+    ("fp32", 1, 16 * 8),     # a one-token prompt has nothing to prefill
+])
+def test_prompt_prefill_gives_the_same_tokens(torch_cuda, oracle, dtype, prompt_len, prefill_rows):
+    """Greedy decoding with the prompt positions before the last going through the layers together: tokens as the
+    oracle's (which feeds the prompt one position at a time) up to each sequence's first near-tie, self-attention
+    keys and values of the prompt positions as after token-by-token feeding."""
+    from tests import gpu_util as G
+    torch = torch_cuda
+    enc_lens = [33, 7, 130, 64, 1]
+    wl = unit_workload(dtype, 256, 4, 64, enc_lens, seed=71, max_new=20, prompt_len=prompt_len)
+    m = oracle.Model(wl.cfg, wl.weights)
+    ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, 20, want_logits=True)
+    first = G.first_near_tie(ref_logits, G.TOL[dtype])
+    outs = {}
+    for rows in (0, prefill_rows):
+        dec = G.make_decoder(wl, prefill_rows=rows)
+        dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+        toks, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), 20)
+        toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+        assert (lens == 20).all()
+        for b in range(len(enc_lens)):
+            assert (toks[b, :first[b]] == ref_t[b, :first[b]]).all(), f"prefill_rows {rows}: sequence {b} differs"
+        kv = [dec.aed_read_self_kv(1, b) for b in (0, len(enc_lens) - 1)]
+        outs[rows] = (toks, kv)
+        dec.close()
+    tol = 1e-5 if dtype == "fp32" else 4e-2
+    for (k0, v0), (k1, v1) in zip(outs[0][1], outs[prefill_rows][1]):
+        P = prompt_len
+        assert np.isfinite(k1).all() and np.isfinite(v1).all()
+        assert np.abs(k0[:P] - k1[:P]).max() <= tol and np.abs(v0[:P] - v1[:P]).max() <= tol
+    print(f"prefill {dtype} P={prompt_len} rows={prefill_rows}: tokens as the oracle's up to step {first.tolist()}")
+
+
 def test_degenerate_shapes_and_reuse(torch_cuda, oracle):
     """Batch of one, one-token prompt, one new token, a decode length that ends exactly on a page boundary,
     EOS as the very first token, repeated greedy calls of different lengths on one batch (the launch graph is
