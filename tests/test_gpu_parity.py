@@ -107,6 +107,25 @@ def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head
     dec.close()
 
 
+@pytest.mark.parametrize("d_model,n_heads,head_dim,batch", [
+    (512, 4, 128, 1750),   # QKV product: 14 x 12 tiles of 128 x 128, K = 512 -> direct-to-LDS 128-tile kernel
+    (256, 4, 64, 3500),    # QKV product: 28 x 6 tiles, K = 256 -> register-staged 128-tile kernel
+])
+def test_very_large_batches_tiled_projections(torch_cuda, oracle, d_model, n_heads, head_dim, batch):
+    """Batches large enough for the 128 x 128 tiled kernels to take the QKV product, LayerNorm folded around it
+    (ragged last row tile); a few teacher-forced steps against the oracle."""
+    from tests import gpu_util as G
+    enc_lens = [1 + (5 * i) % 7 for i in range(batch)]
+    wl = unit_workload("bf16", d_model, n_heads, head_dim, enc_lens, seed=batch, max_new=8)
+    toks = random_tokens(wl.cfg, batch, 4, 6)
+    ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
+    print(f"batch {batch}, d={d_model}: max |dlogit| = {err:.2e}, near ties {near}")
+    dec.close()
+
+
 def test_split_chunks_and_capacity_slack(torch_cuda, oracle):
     """Few long sequences: the work lists cut keys into several chunks per (sequence, head) and
     the last-arriver merge runs; capacities larger than the batch leave unused slots poisoned."""
