@@ -118,6 +118,49 @@ int aedo_num_threads(void)
 }
 
 /* ------------------------------------------------------------------ */
+/* 8-bit E4M3 storage of keys and values (OCP OFP8)                    */
+/* ------------------------------------------------------------------ */
+double aedo_fp8_e4m3_decode(uint8_t code)
+{
+    int sign = code >> 7, ef = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (ef == 15 && m == 7) return NAN;
+    if (ef == 0)
+        v = ldexp((double)m / 8.0, -6); /* subnormal: 0.m * 2^(1 - bias) */
+    else
+        v = ldexp(1.0 + (double)m / 8.0, ef - 7);
+    return sign ? -v : v;
+}
+
+uint8_t aedo_fp8_e4m3_encode(float x)
+{
+    uint8_t sign = signbit(x) ? 0x80 : 0;
+    if (isnan(x)) return (uint8_t)(sign | 0x7f);
+    double a = fabs((double)x);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7e); /* saturate */
+    if (a == 0.0) return sign;
+    int e = ilogb(a); /* a = f * 2^e, 1 <= f < 2 */
+    if (e < -6) e = -6; /* below the smallest normal the spacing stays 2^-9 */
+    /* a in units of the spacing 2^(e-3); rint rounds ties to even (default rounding mode), and an even
+     * count is an even code because the mantissa field is the count's low bits */
+    int q = (int)rint(ldexp(a, 3 - e));
+    if (q < 8) return (uint8_t)(sign | q);          /* subnormal, or zero */
+    if (q == 16) { q = 8; e += 1; }                 /* rounded up into the next binade */
+    return (uint8_t)(sign | ((e + 7) << 3) | (q - 8));
+}
+
+void aedo_fp8_e4m3_encode_array(const float *x, int64_t n, uint8_t *codes)
+{
+    for (int64_t i = 0; i < n; ++i) codes[i] = aedo_fp8_e4m3_encode(x[i]);
+}
+
+/* v[i] <- the value its E4M3 code stands for */
+static void store_as_fp8(double *v, int n)
+{
+    for (int i = 0; i < n; ++i) v[i] = aedo_fp8_e4m3_decode(aedo_fp8_e4m3_encode((float)v[i]));
+}
+
+/* ------------------------------------------------------------------ */
 /* cross-attention memory                                              */
 /* ------------------------------------------------------------------ */
 int aedo_cross_kv(const aedo_config *cfg, const aedo_weights *w, int layer,
@@ -131,6 +174,7 @@ int aedo_cross_kv(const aedo_config *cfg, const aedo_weights *w, int layer,
     for (int t = 0; t < T; ++t) {
         for (int i = 0; i < d; ++i) x[i] = (double)enc[(size_t)t * d + i];
         aedo_linear(x, lw->w_ckv, lw->b_ckv, d, 2 * d, kv);
+        if (cfg->kv_fp8) store_as_fp8(kv, 2 * d);
         memcpy(K_out + (size_t)t * d, kv, sizeof(double) * (size_t)d);
         memcpy(V_out + (size_t)t * d, kv + d, sizeof(double) * (size_t)d);
     }
@@ -211,6 +255,7 @@ static void seq_step(const aedo_config *cfg, const aedo_weights *w, seq_state *s
         /* causal self-attention: the cache holds positions 0..pos */
         aedo_layernorm(s->x, lw->ln1_g, lw->ln1_b, d, eps, s->h);
         aedo_linear(s->h, lw->w_qkv, lw->b_qkv, d, 3 * d, s->qkv);
+        if (cfg->kv_fp8) store_as_fp8(s->qkv + d, 2 * d);
         memcpy(s->Ks[l] + (size_t)pos * d, s->qkv + d, sizeof(double) * (size_t)d);
         memcpy(s->Vs[l] + (size_t)pos * d, s->qkv + 2 * d, sizeof(double) * (size_t)d);
         for (int hd = 0; hd < H; ++hd)
@@ -394,6 +439,7 @@ int aedo_forward_full(const aedo_config *cfg, const aedo_weights *w,
             for (int s = 0; s < S; ++s) {
                 aedo_layernorm(X + (size_t)s * d, lw->ln1_g, lw->ln1_b, d, eps, Hn + (size_t)s * d);
                 aedo_linear(Hn + (size_t)s * d, lw->w_qkv, lw->b_qkv, d, 3 * d, row3);
+                if (cfg->kv_fp8) store_as_fp8(row3 + d, 2 * d);
                 memcpy(Q + (size_t)s * d, row3, sizeof(double) * (size_t)d);
                 memcpy(K + (size_t)s * d, row3 + d, sizeof(double) * (size_t)d);
                 memcpy(Vv + (size_t)s * d, row3 + 2 * d, sizeof(double) * (size_t)d);
@@ -411,6 +457,7 @@ int aedo_forward_full(const aedo_config *cfg, const aedo_weights *w,
                     for (int i = 0; i < d; ++i)
                         encrow[i] = (double)enc_padded[((size_t)b * T_max + t) * d + i];
                     aedo_linear(encrow, lw->w_ckv, lw->b_ckv, d, 2 * d, row3);
+                    if (cfg->kv_fp8) store_as_fp8(row3, 2 * d);
                     memcpy(Kc + (size_t)t * d, row3, sizeof(double) * (size_t)d);
                     memcpy(Vc + (size_t)t * d, row3 + d, sizeof(double) * (size_t)d);
                 }

@@ -40,6 +40,7 @@ typedef struct aedo_config {
     int32_t eos_id;   /* < 0: never stop on EOS */
     int32_t pad_id;   /* written after a sequence has finished */
     float ln_eps, emb_scale;
+    int32_t kv_fp8;   /* nonzero: attention keys and values are stored as 8-bit E4M3 codes (see below) */
 } aedo_config;
 
 typedef struct aedo_layer {
@@ -68,6 +69,20 @@ void aedo_attend(const double *q, const double *K, const double *V, int n_keys, 
                  int stride, double *out, double *probs);
 /* Lowest index of the maximum. */
 int32_t aedo_argmax(const double *a, int n);
+
+/* 8-bit floating point storage of the attention keys and values (an option of
+ * this implementation, not of the paper: it halves the bytes the attention
+ * steps stream).  Format: E4M3 of the OCP 8-bit floating point specification
+ * (OFP8): 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals at
+ * exponent field 0, no infinities, S.1111.111 is NaN, largest magnitude 448.
+ * Encoding takes the value as a float (the precision the product's kernels
+ * hold it in), rounds to the nearest code, ties to the even code, and
+ * saturates: anything beyond 448 becomes +-448.  With cfg.kv_fp8 set, every
+ * key / value element is replaced by decode(encode(.)) at the moment it is
+ * cached; nothing else changes. */
+uint8_t aedo_fp8_e4m3_encode(float x);
+double aedo_fp8_e4m3_decode(uint8_t code);
+void aedo_fp8_e4m3_encode_array(const float *x, int64_t n, uint8_t *codes);
 
 /* Cross-attention memory of one layer for one sequence: K = enc Wk^T + bk,
  * V = enc Wv^T + bv with [Wk; Wv] = w_ckv.  enc [T, d] -> K_out, V_out [T, d]. */

@@ -30,7 +30,7 @@ class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
                  "max_positions", "eos_id", "pad_id")] + \
-               [("ln_eps", C.c_float), ("emb_scale", C.c_float)]
+               [("ln_eps", C.c_float), ("emb_scale", C.c_float), ("kv_fp8", C.c_int32)]
 
 
 class _Layer(C.Structure):
@@ -73,6 +73,12 @@ def lib():
         _lib.aedo_layer_matrix_params.argtypes = [C.POINTER(_Config)]
         _lib.aedo_layer_matrix_params.restype = C.c_int64
         _lib.aedo_num_threads.restype = C.c_int
+        _lib.aedo_fp8_e4m3_encode.argtypes = [C.c_float]
+        _lib.aedo_fp8_e4m3_encode.restype = C.c_uint8
+        _lib.aedo_fp8_e4m3_decode.argtypes = [C.c_uint8]
+        _lib.aedo_fp8_e4m3_decode.restype = C.c_double
+        _lib.aedo_fp8_e4m3_encode_array.argtypes = [_f32p, C.c_int64, C.POINTER(C.c_uint8)]
+        _lib.aedo_fp8_e4m3_encode_array.restype = None
     return _lib
 
 
@@ -116,6 +122,7 @@ class Model:
             setattr(c, n, int(getattr(cfg, n)))
         c.ln_eps = float(cfg.ln_eps)
         c.emb_scale = float(cfg.emb_scale)
+        c.kv_fp8 = int(getattr(cfg, "kv_fp8", 0))
         self.c_cfg = c
         layers = (_Layer * cfg.n_layers)()
         for i, lw in enumerate(weights["layers"]):
@@ -226,6 +233,21 @@ def attend(q, K, V, want_probs: bool = False):
 def argmax(a) -> int:
     a = _f64(a)
     return int(lib().aedo_argmax(_p64(a), a.size))
+
+
+def fp8_e4m3_encode(x) -> np.ndarray:
+    """E4M3 codes (uint8) of an array of float32 values."""
+    x = _f32(x)
+    out = np.empty(x.shape, dtype=np.uint8)
+    lib().aedo_fp8_e4m3_encode_array(_p32(x), x.size, out.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return out
+
+
+def fp8_e4m3_decode(codes) -> np.ndarray:
+    """Values (float64) of an array of E4M3 codes."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    f = lib().aedo_fp8_e4m3_decode
+    return np.array([f(int(c)) for c in codes.ravel()], dtype=np.float64).reshape(codes.shape)
 
 
 def num_threads() -> int:

@@ -76,6 +76,7 @@ class DecoderConfig:
     page_size: int = 16
     norm_type: int = 0
     max_positions: int = 0
+    kv_fp8: int = 0  # 1: attention keys and values are stored as 8-bit E4M3 codes (bf16 models only)
 
     def __post_init__(self):
         if self.max_positions <= 0:
