@@ -315,6 +315,24 @@ int aedo_decode_forced(const aedo_config *cfg, const aedo_weights *w,
     return 0;
 }
 
+int aedo_self_kv(const aedo_config *cfg, const aedo_weights *w, const float *enc, int T,
+                 const int32_t *tokens, int S, int layer, double *K_out, double *V_out)
+{
+    if (!config_ok(cfg) || !w || !enc || !tokens || !K_out || !V_out || T < 1) return -1;
+    if (S < 1 || S > cfg->max_positions || layer < 0 || layer >= cfg->n_layers) return -1;
+    for (int i = 0; i < S; ++i)
+        if (tokens[i] < 0 || tokens[i] >= cfg->vocab) return -1;
+    int d = cfg->d_model;
+    double *logits = (double *)malloc(sizeof(double) * (size_t)cfg->vocab);
+    seq_state *s = seq_new(cfg, w, enc, T, S);
+    for (int t = 0; t < S; ++t) seq_step(cfg, w, s, tokens[t], logits);
+    memcpy(K_out, s->Ks[layer], sizeof(double) * (size_t)S * d);
+    memcpy(V_out, s->Vs[layer], sizeof(double) * (size_t)S * d);
+    seq_free(cfg, s);
+    free(logits);
+    return 0;
+}
+
 int aedo_greedy_decode(const aedo_config *cfg, const aedo_weights *w,
                        const float *enc, const int32_t *enc_lens, int B,
                        const int32_t *prompt, int P, int max_new,

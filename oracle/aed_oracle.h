@@ -96,6 +96,11 @@ int aedo_decode_forced(const aedo_config *cfg, const aedo_weights *w,
                        const float *enc, const int32_t *enc_lens, int B,
                        const int32_t *tokens, int S, double *logits_out);
 
+/* The self-attention cache of one layer after one sequence (enc [T, d]) has
+ * been fed tokens[0..S-1]: the keys and values of those positions, [S, d]. */
+int aedo_self_kv(const aedo_config *cfg, const aedo_weights *w, const float *enc, int T,
+                 const int32_t *tokens, int S, int layer, double *K_out, double *V_out);
+
 /* Greedy decoding.  prompt [B, P]; emits at most max_new tokens per sequence.
  * max_new_per_seq (may be NULL; needs eos_id >= 0): sequence b's
  * max_new_per_seq[b]-th emitted token is forced to eos_id.  A sequence

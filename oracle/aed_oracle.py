@@ -70,6 +70,8 @@ def lib():
                                             _f64p]
         _lib.aedo_forward_full.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), _f32p, C.c_int,
                                            _i32p, C.c_int, _i32p, C.c_int, _i32p, _f64p]
+        _lib.aedo_self_kv.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), _f32p, C.c_int, _i32p, C.c_int,
+                                      C.c_int, _f64p, _f64p]
         _lib.aedo_layer_matrix_params.argtypes = [C.POINTER(_Config)]
         _lib.aedo_layer_matrix_params.restype = C.c_int64
         _lib.aedo_num_threads.restype = C.c_int
@@ -190,6 +192,18 @@ class Model:
                                  _p64(K), _p64(V))
         if rc != 0:
             raise ValueError(f"aedo_cross_kv: bad argument ({rc})")
+        return K, V
+
+    def self_kv(self, layer: int, enc, tokens):
+        """Self-attention keys and values [S, d] of `layer` after one sequence was fed tokens [S]."""
+        enc, tokens = _f32(enc), _i32(tokens)
+        S, d = tokens.shape[0], self.cfg.d_model
+        K = np.zeros((S, d), dtype=np.float64)
+        V = np.zeros((S, d), dtype=np.float64)
+        rc = lib().aedo_self_kv(C.byref(self.c_cfg), C.byref(self.c_w), _p32(enc), enc.shape[0], _pi(tokens), S,
+                                int(layer), _p64(K), _p64(V))
+        if rc != 0:
+            raise ValueError(f"aedo_self_kv: bad argument ({rc})")
         return K, V
 
     def layer_matrix_params(self) -> int:

@@ -151,6 +151,9 @@ def test_self_attention_reads_quantised_keys_and_values(oracle):
         x = x + f(lw["w_o"]) @ att + f(lw["b_o"])
         logits = f(w["w_out"]) @ ln(x, f(w["lnf_g"]), f(w["lnf_b"]), cfg.ln_eps) + f(w["b_out"])
         assert np.abs(got[s] - logits).max() < 1e-10
+    # the cache accessor returns exactly those keys and values
+    Kc, Vc = oracle.Model(cfg, w).self_kv(0, wl.enc, toks[0])
+    assert np.array_equal(Kc, np.stack(Ks)) and np.array_equal(Vc, np.stack(Vs))
     # the option is not a no-op on this input
     wl0 = small_workload(seed=21, n_layers=1, enc_lens=(4,), batch=1)
     exact = oracle.Model(wl0.cfg, w).decode_forced(wl.enc, wl.enc_lens, toks)[0]

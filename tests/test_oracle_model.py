@@ -270,3 +270,23 @@ def test_cross_kv_is_the_linear_map(oracle):
     lw = wl.weights["layers"][1]
     ref = enc.astype(np.float64) @ lw["w_ckv"].astype(np.float64).T + lw["b_ckv"]
     assert np.abs(K - ref[:, :d]).max() < 1e-12 and np.abs(V - ref[:, d:]).max() < 1e-12
+
+
+def test_self_kv_of_the_first_layer_is_the_projection_of_the_embedding(oracle):
+    wl = small_workload(seed=12)
+    cfg, w = wl.cfg, wl.weights
+    m = oracle.Model(cfg, w)
+    d = cfg.d_model
+    toks = np.array([4, 9, 1, 30, 2], np.int32)
+    K, V = m.self_kv(0, wl.enc[:wl.enc_lens[0]], toks)
+    lw = w["layers"][0]
+    for s, t in enumerate(toks):
+        x = cfg.emb_scale * w["tok_emb"][t].astype(np.float64) + w["pos_emb"][s]
+        mu = x.mean()
+        h = (x - mu) / np.sqrt(((x - mu) ** 2).mean() + float(np.float32(cfg.ln_eps))) * lw["ln1_g"] + lw["ln1_b"]
+        qkv = lw["w_qkv"].astype(np.float64) @ h + lw["b_qkv"]
+        assert np.abs(K[s] - qkv[d:2 * d]).max() < 1e-12 and np.abs(V[s] - qkv[2 * d:]).max() < 1e-12
+    # deeper layers: the cache is what attention reads, so feeding one token fewer gives a prefix
+    K1, V1 = m.self_kv(1, wl.enc[:wl.enc_lens[0]], toks)
+    K1s, V1s = m.self_kv(1, wl.enc[:wl.enc_lens[0]], toks[:3])
+    assert np.array_equal(K1[:3], K1s) and np.array_equal(V1[:3], V1s)
