@@ -70,6 +70,14 @@ typedef struct aed_config {
     int32_t pad_id;        /* written to out_tokens after a sequence has finished */
     float ln_eps, emb_scale;
     int32_t prefill_rows;  /* capacity: rows of one prompt-prefill pass (see aed_greedy_decode); 0 = none */
+    int32_t kv_fp8;        /* 1: the self- and cross-attention caches hold 8-bit floating point codes instead of
+                              dtype elements, which halves the bytes the two attention steps stream (bfloat16
+                              models only, else AED_EUNSUPPORTED).  Format: E4M3 of the OCP 8-bit floating point
+                              specification (bias 7, subnormals, no infinities, largest magnitude 448); a key or
+                              value element is rounded from float32 to the nearest code, ties to even, and
+                              saturates at +-448, when it is written to the cache; no scale factor.  An option of
+                              this library, not part of the paper's method; results differ from kv_fp8 = 0 by the
+                              storage rounding.  0: caches in dtype. */
 } aed_config;
 
 /* DEVICE pointers, element type per aed_config.dtype. */

@@ -36,7 +36,8 @@ class AedConfig(C.Structure):
     _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_int32) for n in (
         "n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "max_positions", "dtype", "norm_type",
         "page_size", "max_batch", "max_total_enc_frames", "max_dec_len", "kv_pages", "eos_id", "pad_id")] + [
-        ("ln_eps", C.c_float), ("emb_scale", C.c_float), ("prefill_rows", C.c_int32)]
+        ("ln_eps", C.c_float), ("emb_scale", C.c_float), ("prefill_rows", C.c_int32),
+        ("kv_fp8", C.c_int32)]
 
 
 class AedLayerWeights(C.Structure):
@@ -101,6 +102,7 @@ def make_config(cfg, max_batch: int, max_total_enc_frames: int, max_dec_len: int
                                                                       int(max_dec_len), int(kv_pages))
     c.ln_eps, c.emb_scale = float(cfg.ln_eps), float(cfg.emb_scale)
     c.prefill_rows = int(prefill_rows)
+    c.kv_fp8 = int(getattr(cfg, "kv_fp8", 0))
     return c
 
 

@@ -65,6 +65,8 @@ aed_status check_config(const aed_config* c, std::string& err) {
     if (c->vocab % 64 != 0) return unsup("vocab must be a multiple of 64");
     if (c->max_batch > 65535) return unsup("max_batch above 65535");
     if (c->prefill_rows < 0 || c->prefill_rows > 65535) return bad("prefill_rows must be in [0, 65535]");
+    if (c->kv_fp8 != 0 && c->kv_fp8 != 1) return bad("kv_fp8 must be 0 or 1");
+    if (c->kv_fp8 && c->dtype != 1) return unsup("8-bit key / value caches go with bfloat16 models only");
     return AED_OK;
 }
 
@@ -118,10 +120,11 @@ void make_layout(const aed_config* c, Layout* L) {
     L->v_cur_tok = take(Ba * 4);
     L->v_page_table = take(c->prefill_rows > 0 ? Ba * (size_t)L->max_pages * 4 : 0);
     L->v_items = take(c->prefill_rows > 0 ? (size_t)L->max_items * kMaxPrefillPositions * 16 : 0);
-    L->k_pool = take(L->pool_layer_elems * c->n_layers * e);
-    L->v_pool = take(L->pool_layer_elems * c->n_layers * e);
-    L->kc = take(L->cross_layer_elems * c->n_layers * e);
-    L->vc = take(L->cross_layer_elems * c->n_layers * e);
+    const size_t ekv = c->kv_fp8 ? 1 : e;  // bytes per cached key / value element
+    L->k_pool = take(L->pool_layer_elems * c->n_layers * ekv);
+    L->v_pool = take(L->pool_layer_elems * c->n_layers * ekv);
+    L->kc = take(L->cross_layer_elems * c->n_layers * ekv);
+    L->vc = take(L->cross_layer_elems * c->n_layers * ekv);
     // every weight matrix once more, in MFMA fragment order
     L->w_frag = take(((size_t)c->n_layers * (8 * d * d + 2 * d * (size_t)c->d_ffn) + (size_t)c->vocab * d) * e);
     // the batch's encoder states in fragment order (A operand of the cross K/V GEMMs), whole 256-row tiles
@@ -144,6 +147,7 @@ struct aed_decoder {
     aed_config cfg;
     Dtype dt;
     size_t esz;
+    size_t kv_esz;  // bytes per cached key / value element: esz, or 1 for E4M3 codes
     Layout lay;
     std::vector<aed_layer_weights> layers;  // caller's pointers (biases, LayerNorm, embeddings are used in place)
     aed_weights w;
@@ -249,6 +253,7 @@ GemmArgs gemm_base(const aed_decoder* d) {
     g.n_heads = d->cfg.n_heads;
     g.head_dim = d->cfg.head_dim;
     g.d_model = d->cfg.d_model;
+    g.kv_fp8 = d->cfg.kv_fp8;
     return g;
 }
 
@@ -280,8 +285,8 @@ hipError_t k_ln_qkv(aed_decoder* d, int l) {
     g.W = d->fw[l].w_qkv; g.bias = w.b_qkv; g.ln_g = w.ln1_g; g.ln_b = w.ln1_b;
     g.N = 3 * d->cfg.d_model; g.K = d->cfg.d_model;
     g.out = d->at<float>(d->lay.q);
-    g.k_pool = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
-    g.v_pool = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
+    g.k_pool = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->kv_esz;
+    g.v_pool = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->kv_esz;
     g.page_table = d->at<int>(d->lay.page_table);
     g.max_pages = d->lay.max_pages;
     g.seq_len = d->at<int>(d->lay.seq_len);
@@ -305,14 +310,15 @@ AttnArgs attn_base(const aed_decoder* d) {
     a.n_heads = d->cfg.n_heads;
     a.head_dim = d->cfg.head_dim;
     a.batch = d->batch;
+    a.kv_fp8 = d->cfg.kv_fp8;
     a.scale_log2e = (float)(1.4426950408889634 / sqrt((double)d->cfg.head_dim));
     return a;
 }
 
 hipError_t k_self_attn(aed_decoder* d, int l) {
     AttnArgs a = attn_base(d);
-    a.K = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
-    a.V = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->esz;
+    a.K = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->kv_esz;
+    a.V = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->kv_esz;
     a.page_table = d->at<int>(d->lay.page_table);
     a.max_pages = d->lay.max_pages;
     a.seq_len = d->at<int>(d->lay.seq_len);
@@ -356,8 +362,8 @@ hipError_t k_ln_crossq(aed_decoder* d, int l) {
 
 hipError_t k_cross_attn(aed_decoder* d, int l) {
     AttnArgs a = attn_base(d);
-    a.K = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
-    a.V = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
+    a.K = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->kv_esz;
+    a.V = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->kv_esz;
     a.items = d->at<int4>(d->lay.items);
     a.n_items = d->n_items;
     a.enc_off = d->at<int>(d->lay.enc_off);
@@ -403,8 +409,8 @@ hipError_t k_cross_kv(aed_decoder* d, int l, long long rows, const int* frame_ma
     g.out_row_map = frame_map;
     g.a_rows = (int)align_up((size_t)d->cfg.max_total_enc_frames, 256);
     g.M = (int)rows; g.N = 2 * d->cfg.d_model; g.K = d->cfg.d_model;
-    g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->esz;
-    g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->esz;
+    g.kc = d->ws + d->lay.kc + (size_t)l * d->lay.cross_layer_elems * d->kv_esz;
+    g.vc = d->ws + d->lay.vc + (size_t)l * d->lay.cross_layer_elems * d->kv_esz;
     g.t_cap = d->cfg.max_total_enc_frames;
     return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);  // LDS-tiled kernel from 512 rows (bf16)
 }
@@ -686,6 +692,7 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
     d->cfg = *cfg;
     d->dt = cfg->dtype == 1 ? kBF16 : kF32;
     d->esz = cfg->dtype == 1 ? 2 : 4;
+    d->kv_esz = cfg->kv_fp8 ? 1 : d->esz;
     d->lay = L;
     d->layers.assign(weights->layers, weights->layers + cfg->n_layers);
     d->w = *weights;
@@ -1112,8 +1119,24 @@ int64_t aed_layer_matrix_params(const aed_config* c) {
 
 // ---------------------------------------------------------------- inspection / measurement
 namespace {
-void to_f32_host(const void* src, size_t n, bool bf16, float* dst) {
-    if (!bf16) { memcpy(dst, src, n * 4); return; }
+// Value of an E4M3 code (OCP 8-bit floating point: 4 exponent bits with bias 7, 3 mantissa bits, subnormals, no
+// infinities, S.1111.111 is NaN).
+float e4m3_value(uint8_t c) {
+    const int ef = (c >> 3) & 15, m = c & 7;
+    float v;
+    if (ef == 15 && m == 7) v = NAN;
+    else if (ef == 0) v = ldexpf((float)m, -9);
+    else v = ldexpf((float)(8 + m), ef - 10);
+    return (c & 0x80) ? -v : v;
+}
+// esz: bytes per element (4: float, 2: bfloat16, 1: E4M3 code)
+void to_f32_host(const void* src, size_t n, size_t esz, float* dst) {
+    if (esz == 4) { memcpy(dst, src, n * 4); return; }
+    if (esz == 1) {
+        const uint8_t* p = static_cast<const uint8_t*>(src);
+        for (size_t i = 0; i < n; ++i) dst[i] = e4m3_value(p[i]);
+        return;
+    }
     const uint16_t* p = static_cast<const uint16_t*>(src);
     for (size_t i = 0; i < n; ++i) {
         uint32_t u = (uint32_t)p[i] << 16;
@@ -1131,15 +1154,15 @@ aed_status aed_read_cross_kv(aed_decoder* d, int32_t layer, int32_t seq, float* 
         return fail(d, AED_EINVAL, "bad layer / seq / buffer");
     HIP_TRY(d, hipStreamSynchronize(d->stream));
     const int T = d->enc_lens[seq], Dh = d->cfg.head_dim, H = d->cfg.n_heads, dm = d->cfg.d_model;
-    std::vector<char> tmp((size_t)T * Dh * d->esz);
+    std::vector<char> tmp((size_t)T * Dh * d->kv_esz);
     std::vector<float> f((size_t)T * Dh);
     for (int which = 0; which < 2; ++which) {
-        const char* base = d->ws + (which ? d->lay.vc : d->lay.kc) + (size_t)layer * d->lay.cross_layer_elems * d->esz;
+        const char* base = d->ws + (which ? d->lay.vc : d->lay.kc) + (size_t)layer * d->lay.cross_layer_elems * d->kv_esz;
         float* out = which ? v_out : k_out;
         for (int h = 0; h < H; ++h) {
-            const char* src = base + ((size_t)h * d->cfg.max_total_enc_frames + d->enc_off[seq]) * Dh * d->esz;
+            const char* src = base + ((size_t)h * d->cfg.max_total_enc_frames + d->enc_off[seq]) * Dh * d->kv_esz;
             HIP_TRY(d, hipMemcpy(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost));
-            to_f32_host(tmp.data(), f.size(), d->dt == kBF16, f.data());
+            to_f32_host(tmp.data(), f.size(), d->kv_esz, f.data());
             for (int t = 0; t < T; ++t) memcpy(out + (size_t)t * dm + h * Dh, f.data() + (size_t)t * Dh, Dh * 4);
         }
     }
@@ -1158,17 +1181,17 @@ aed_status aed_read_self_kv(aed_decoder* d, int32_t layer, int32_t seq, float* k
     n = std::min(n, d->cfg.max_dec_len);
     *n_positions = n;
     const int Dh = d->cfg.head_dim, H = d->cfg.n_heads, dm = d->cfg.d_model;
-    std::vector<char> tmp((size_t)kPage * Dh * d->esz);
+    std::vector<char> tmp((size_t)kPage * Dh * d->kv_esz);
     std::vector<float> f((size_t)kPage * Dh);
     for (int which = 0; which < 2; ++which) {
-        const char* base = d->ws + (which ? d->lay.v_pool : d->lay.k_pool) + (size_t)layer * d->lay.pool_layer_elems * d->esz;
+        const char* base = d->ws + (which ? d->lay.v_pool : d->lay.k_pool) + (size_t)layer * d->lay.pool_layer_elems * d->kv_esz;
         float* out = which ? v_out : k_out;
         for (int blk = 0; blk * kPage < n; ++blk) {
             const int page = d->page_table[(size_t)seq * d->lay.max_pages + blk];
             for (int h = 0; h < H; ++h) {
-                const char* src = base + ((size_t)page * H + h) * kPage * Dh * d->esz;
+                const char* src = base + ((size_t)page * H + h) * kPage * Dh * d->kv_esz;
                 HIP_TRY(d, hipMemcpy(tmp.data(), src, tmp.size(), hipMemcpyDeviceToHost));
-                to_f32_host(tmp.data(), f.size(), d->dt == kBF16, f.data());
+                to_f32_host(tmp.data(), f.size(), d->kv_esz, f.data());
                 for (int s = 0; s < kPage && blk * kPage + s < n; ++s)
                     memcpy(out + (size_t)(blk * kPage + s) * dm + h * Dh, f.data() + (size_t)s * Dh, Dh * 4);
             }
@@ -1204,7 +1227,7 @@ aed_status aed_kernel_work(aed_decoder* d, int32_t cls, double* bytes, double* f
     if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
     if (!bytes || !flops) return fail(d, AED_EINVAL, "NULL output");
     HIP_TRY(d, hipStreamSynchronize(d->stream));
-    const double e = (double)d->esz, B = d->batch, dm = d->cfg.d_model, F = d->cfg.d_ffn, V = d->cfg.vocab;
+    const double e = (double)d->esz, ekv = (double)d->kv_esz, B = d->batch, dm = d->cfg.d_model, F = d->cfg.d_ffn, V = d->cfg.vocab;
     // ln: the product follows a LayerNorm.  float32 mode reads the float32 rows and the gain / shift vectors;
     // bfloat16 mode reads the rows' shadow, their tile statistics and shifts, and the folded vectors c1, c2.
     // resid: a residual update (float32 rows read and written); bfloat16 mode also writes shadow and statistics.
@@ -1219,13 +1242,13 @@ aed_status aed_kernel_work(aed_decoder* d, int32_t cls, double* bytes, double* f
         *flops = 2 * M * N * K;
     };
     switch (cls) {
-        case AED_K_LN_QKV: gemm(B, 3 * dm, dm, 4, 0, true, false); *bytes += B * dm * 4 + 2 * B * dm * e; break;
+        case AED_K_LN_QKV: gemm(B, 3 * dm, dm, 4, 0, true, false); *bytes += B * dm * 4 + 2 * B * dm * ekv; break;
         case AED_K_SELF_OUT: case AED_K_CROSS_OUT: gemm(B, dm, dm, e, 8, false, true); break;
         case AED_K_LN_CROSSQ: gemm(B, dm, dm, 4, 4, true, false); break;
         case AED_K_LN_FFN1: gemm(B, F, dm, 4, e, true, false); break;
         case AED_K_FFN2: gemm(B, dm, F, e, 8, false, true); break;
         case AED_K_LN_VOCAB: gemm(B, V, dm, 4, 4, true, false); break;
-        case AED_K_CROSS_KV: gemm((double)d->total_enc, 2 * dm, dm, e, e, false, false); break;
+        case AED_K_CROSS_KV: gemm((double)d->total_enc, 2 * dm, dm, e, ekv, false, false); break;
         case AED_K_SELF_ATTN: case AED_K_CROSS_ATTN: {
             double keys = 0;
             if (cls == AED_K_CROSS_ATTN) keys = (double)d->total_enc;
@@ -1234,7 +1257,7 @@ aed_status aed_kernel_work(aed_decoder* d, int32_t cls, double* bytes, double* f
                 HIP_TRY(d, hipMemcpy(len.data(), d->at<int>(d->lay.seq_len), (size_t)d->batch * 4, hipMemcpyDeviceToHost));
                 for (int b = 0; b < d->batch; ++b) keys += std::min(len[b], d->cfg.max_dec_len - 1) + 1;
             }
-            *bytes = keys * 2 * dm * e + B * dm * 4 + B * dm * e;
+            *bytes = keys * 2 * dm * ekv + B * dm * 4 + B * dm * e;
             *flops = keys * 4 * dm;
             break;
         }

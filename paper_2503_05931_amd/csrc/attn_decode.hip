@@ -16,8 +16,10 @@
 // one is consumed).
 // A wavefront reads a block as 4 keys per load instruction: lane (r, g) loads
 // 16 bytes (or 8) -- the slice r of head_dim -- of key 4 i + g, i = 0..3, so
-// each instruction covers 4 whole rows (1 KB for bf16 head_dim 128).  The dot
-// products are reduced over the 16 lanes of a DPP row, the running softmax
+// each instruction covers 4 whole rows (1 KB for bf16 head_dim 128).  When the
+// caches hold 8-bit E4M3 codes a key row is half as long: 8 lanes share a key
+// and an instruction covers 8 keys, so the loads keep their 16 bytes per lane.
+// The dot products are reduced over the lanes of a key, the running softmax
 // (max, sum, weighted values) is kept per wavefront in base-2 exponent form,
 // the wavefronts are merged through LDS.  Sequences of this workload are short
 // (at most 500 encoder frames, a few hundred decoded tokens), so one workgroup
@@ -37,6 +39,9 @@ template <> struct RawRow<bf16_t, 8> { bf16x8 v; };
 template <> struct RawRow<bf16_t, 4> { bf16x4 v; };
 template <> struct RawRow<float, 8> { f32x4 v[2]; };
 template <> struct RawRow<float, 4> { f32x4 v[1]; };
+typedef unsigned char fp8_t;  // one E4M3 code (OCP 8-bit floating point; the conversion instructions' format)
+template <> struct RawRow<fp8_t, 16> { u32x4 v; };
+template <> struct RawRow<fp8_t, 8> { u32x2 v; };
 
 template <int EPL> __device__ __forceinline__ RawRow<bf16_t, EPL> load_raw(const bf16_t* p) {
     RawRow<bf16_t, EPL> r;
@@ -49,13 +54,56 @@ template <int EPL> __device__ __forceinline__ RawRow<float, EPL> load_raw(const 
     for (int i = 0; i < EPL / 4; ++i) r.v[i] = reinterpret_cast<const f32x4*>(p)[i];
     return r;
 }
+template <int EPL> __device__ __forceinline__ RawRow<fp8_t, EPL> load_raw(const fp8_t* p) {
+    RawRow<fp8_t, EPL> r;
+    r.v = *reinterpret_cast<const decltype(r.v)*>(p);
+    return r;
+}
+// The row slice as floats.  bf16 / float rows are converted element by element where they are used (the
+// compiler keeps them packed until then); E4M3 codes come out of the conversion instruction two at a time.
+template <int EPL> struct Unpacked { float y[EPL]; __device__ __forceinline__ float operator[](int e) const { return y[e]; } };
+template <int EPL> __device__ __forceinline__ const RawRow<bf16_t, EPL>& unpack(const RawRow<bf16_t, EPL>& r) { return r; }
+template <int EPL> __device__ __forceinline__ const RawRow<float, EPL>& unpack(const RawRow<float, EPL>& r) { return r; }
+template <int EPL> __device__ __forceinline__ Unpacked<EPL> unpack(const RawRow<fp8_t, EPL>& r) {
+    Unpacked<EPL> u;
+#pragma unroll
+    for (int w = 0; w < EPL / 4; ++w) {  // bytes 0,1 of a word, then bytes 2,3
+        const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.v[w], false);
+        const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.v[w], true);
+        u.y[4 * w] = lo[0]; u.y[4 * w + 1] = lo[1]; u.y[4 * w + 2] = hi[0]; u.y[4 * w + 3] = hi[1];
+    }
+    return u;
+}
 template <int EPL> __device__ __forceinline__ float raw_at(const RawRow<bf16_t, EPL>& r, int e) { return (float)r.v[e]; }
 template <int EPL> __device__ __forceinline__ float raw_at(const RawRow<float, EPL>& r, int e) { return r.v[e >> 2][e & 3]; }
+template <int EPL> __device__ __forceinline__ float raw_at(const Unpacked<EPL>& u, int e) { return u.y[e]; }
 
-template <typename T, int DH, bool SELF, int NW>
+// sum over the LPK lanes that share a key (LPK consecutive lanes of a DPP row)
+template <int LPK> __device__ __forceinline__ float key_sum(float v) {
+    v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);  // row_half_mirror
+    if constexpr (LPK == 16) v += dpp_mov<0x140>(v);  // row_mirror
+    return v;
+}
+// sum / max over the 64 / LPK keys that the lanes of a wavefront hold side by side
+template <int LPK> __device__ __forceinline__ float keys_sum(float v) {
+    if constexpr (LPK == 8) v += dpp_mov<0x128>(v);  // row_ror 8: lane l ^ 8
+    return rows4_sum(v);
+}
+template <int LPK> __device__ __forceinline__ float keys_max(float v) {
+    if constexpr (LPK == 8) v = fmaxf(v, dpp_mov<0x128>(v));
+    return rows4_max(v);
+}
+
+// T: type of the output rows (and of the caches unless KV says otherwise); KV: what the caches hold;
+// LPK: lanes that share a key row.
+template <typename T, typename KV, int LPK, int DH, bool SELF, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
-    constexpr int EPL = DH / 16;  // head_dim elements per lane
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
+    constexpr int EPL = DH / LPK;   // head_dim elements per lane
+    constexpr int KPI = 64 / LPK;   // keys per load instruction
+    constexpr int NI = 16 / KPI;    // load instructions per 16-key block
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane % LPK, g = lane / LPK;
     const int h = blockIdx.x, H = a.n_heads;
 
     // Work item.  Cross-attention: from the host-built list (longest first, so the long sequences
@@ -89,23 +137,23 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
         fin = a.finished[b];  // tested after the first loads have been issued
     }
 
-    const T* __restrict__ Kb = static_cast<const T*>(a.K);
-    const T* __restrict__ Vb = static_cast<const T*>(a.V);
+    const KV* __restrict__ Kb = static_cast<const KV*>(a.K);
+    const KV* __restrict__ Vb = static_cast<const KV*>(a.V);
     size_t cross_base = 0;
     if constexpr (!SELF) cross_base = ((size_t)h * a.t_cap + row0) * DH;
     const int n_blocks = (n + 15) >> 4;
     const int* __restrict__ pages = SELF ? a.page_table + (size_t)b * a.max_pages + (start >> 4) : nullptr;
 
-    typedef RawRow<T, EPL> Raw;
-    // element offset of this lane's slice of key (4 i + g) of block kb (clamped to the valid keys)
+    typedef RawRow<KV, EPL> Raw;
+    // element offset of this lane's slice of key (KPI i + g) of block kb (clamped to the valid keys)
     auto fetch = [&](int kb, Raw* kf, Raw* vf) {
         size_t blk_base;
         if constexpr (SELF) blk_base = ((size_t)(kb == wave ? first_page : pages[kb]) * H + h) * kPage * DH;
         else blk_base = cross_base + (size_t)kb * 16 * DH;
         const int last = n - 1 - kb * 16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = i * 4 + g;
+        for (int i = 0; i < NI; ++i) {
+            const int j = i * KPI + g;
             const int jc = j < last ? j : last;  // never read past the valid keys
             const size_t off = blk_base + (size_t)jc * DH + r * EPL;
             kf[i] = load_raw<EPL>(Kb + off);
@@ -128,35 +176,37 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
 
     auto consume = [&](int kb, const Raw* kf, const Raw* vf) {
         const int last = n - 1 - kb * 16;
-        float s[4];
+        float s[NI];
         float m_blk = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
+            const auto& kx = unpack<EPL>(kf[i]);
             float d = 0.f;
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) d = fmaf(q[e], raw_at<EPL>(kf[i], e), d);
-            d = row16_sum(d);
-            s[i] = (i * 4 + g <= last) ? d : -INFINITY;
+            for (int e = 0; e < EPL; ++e) d = fmaf(q[e], raw_at<EPL>(kx, e), d);
+            d = key_sum<LPK>(d);
+            s[i] = (i * KPI + g <= last) ? d : -INFINITY;
             m_blk = fmaxf(m_blk, s[i]);
         }
-        m_blk = rows4_max(m_blk);
+        m_blk = keys_max<LPK>(m_blk);
         const float m_new = fmaxf(m_run, m_blk);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);  // first block: exp2(-inf) = 0
         l_run *= alpha;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] *= alpha;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const float p = __builtin_amdgcn_exp2f(s[i] - m_new);
             l_run += p;
+            const auto& vx = unpack<EPL>(vf[i]);
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, raw_at<EPL>(vf[i], e), acc[e]);
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, raw_at<EPL>(vx, e), acc[e]);
         }
         m_run = m_new;
     };
 
     // two blocks in flight per wavefront: fetch block i+1 while block i is consumed
-    Raw k0[4], v0[4], k1[4], v1[4];
+    Raw k0[NI], v0[NI], k1[NI], v1[NI];
     int kb = wave;
     if (kb < n_blocks) fetch(kb, k0, v0);
     if constexpr (!SELF) {
@@ -171,10 +221,10 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
         consume(kb, k1, v1);
         kb += NW;
     }
-    // lanes of different rows g hold different keys: add them up
-    l_run = rows4_sum(l_run);
+    // lanes of different groups g hold different keys: add them up
+    l_run = keys_sum<LPK>(l_run);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = rows4_sum(acc[e]);
+    for (int e = 0; e < EPL; ++e) acc[e] = keys_sum<LPK>(acc[e]);
 
     __shared__ float sm_acc[NW][DH];
     __shared__ float sm_m[NW], sm_l[NW];
@@ -247,19 +297,27 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
 
 // Wavefronts per workgroup: 8 when the launch has few workgroups (the longest
 // sequence sets the kernel's duration), 4 when there are plenty.
-template <typename T, bool SELF>
-static hipError_t launch_dh(const AttnArgs& a, dim3 grid, hipStream_t s) {
+template <typename T, typename KV, int LPK, bool SELF>
+static hipError_t launch_kv(const AttnArgs& a, dim3 grid, hipStream_t s) {
     const bool wide = (size_t)grid.x * grid.y * grid.z <= 1024;
     if (a.head_dim == 128) {
-        if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF, 8>), grid, dim3(512), 0, s, a);
-        else hipLaunchKernelGGL((attn_decode_kernel<T, 128, SELF, 4>), grid, dim3(256), 0, s, a);
+        if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, KV, LPK, 128, SELF, 8>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((attn_decode_kernel<T, KV, LPK, 128, SELF, 4>), grid, dim3(256), 0, s, a);
     } else if (a.head_dim == 64) {
-        if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF, 8>), grid, dim3(512), 0, s, a);
-        else hipLaunchKernelGGL((attn_decode_kernel<T, 64, SELF, 4>), grid, dim3(256), 0, s, a);
+        if (wide) hipLaunchKernelGGL((attn_decode_kernel<T, KV, LPK, 64, SELF, 8>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((attn_decode_kernel<T, KV, LPK, 64, SELF, 4>), grid, dim3(256), 0, s, a);
     } else {
         return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+template <typename T, bool SELF>
+static hipError_t launch_dh(const AttnArgs& a, dim3 grid, hipStream_t s) {
+    if (a.kv_fp8) {
+        if constexpr (sizeof(T) == 2) return launch_kv<T, fp8_t, 8, SELF>(a, grid, s);
+        else return hipErrorInvalidValue;  // 8-bit caches go with bfloat16 models only
+    }
+    return launch_kv<T, T, 16, SELF>(a, grid, s);
 }
 
 hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s) {

@@ -77,6 +77,16 @@ __device__ __forceinline__ void mma(f32x4& acc, const Frag16<float>& w, const Fr
     for (int i = 0; i < 16; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w.v[i], a.v[i], acc, 0, 0, 0);
 }
 
+// Four consecutive cache elements as 8-bit E4M3 codes (OCP 8-bit floating point: bias 7, no infinities, largest
+// magnitude 448): round to nearest even, done by the conversion instruction; saturation is done here.
+__device__ __forceinline__ void store4_fp8(unsigned char* p, f32x4 s) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[i] = fminf(fmaxf(s[i], -448.f), 448.f);
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(s[0], s[1], 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(s[2], s[3], w, true);
+    *reinterpret_cast<int*>(p) = w;
+}
+
 // One lane's four consecutive outputs C[m][n .. n+3] (bias already added) go where the epilogue says.
 // res: the residual read earlier from the same place (EPI_RESID only).
 template <typename T, int EPI>
@@ -99,17 +109,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int m, int n, f
             const int h = c / a.head_dim, e = c % a.head_dim;
             const int pos = a.seq_len[m];
             const int page = a.page_table[(size_t)m * a.max_pages + (pos >> 4)];
-            T* pool = static_cast<T*>(which ? a.v_pool : a.k_pool);
-            store4(pool + (((size_t)page * a.n_heads + h) * kPage + (pos & 15)) * a.head_dim + e, s);
+            const size_t at = (((size_t)page * a.n_heads + h) * kPage + (pos & 15)) * a.head_dim + e;
+            if (a.kv_fp8) store4_fp8(static_cast<unsigned char*>(which ? a.v_pool : a.k_pool) + at, s);
+            else store4(static_cast<T*>(which ? a.v_pool : a.k_pool) + at, s);
         }
     } else {  // EPI_CROSSKV
         const int d = a.d_model;
         const int which = n >= d;
         const int c = n - (which ? d : 0);
         const int h = c / a.head_dim, e = c % a.head_dim;
-        T* dst = static_cast<T*>(which ? a.vc : a.kc);
         const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
-        store4(dst + ((size_t)h * a.t_cap + frame) * a.head_dim + e, s);
+        const size_t at = ((size_t)h * a.t_cap + frame) * a.head_dim + e;
+        if (a.kv_fp8) store4_fp8(static_cast<unsigned char*>(which ? a.vc : a.kc) + at, s);
+        else store4(static_cast<T*>(which ? a.vc : a.kc) + at, s);
     }
 }
 

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
 // bf16, EPI_CROSSKV.  A (fragment order) must hold whole 256-row tiles; N % 256 == 0; K % 64 == 0, K >= 256;
 // head_dim 64 or 128 and d_model a multiple of 64, so that a wavefront's 64 columns stay inside one head.
 hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s) {
-    if (a.M < 1 || a.N % kBN != 0 || a.K % 64 != 0 || a.K < 256 || a.d_model % 64 != 0 ||
+    if (a.M < 1 || a.N % kBN != 0 || a.K % 64 != 0 || a.K < 256 || a.d_model % 64 != 0 || a.kv_fp8 ||
         (a.head_dim != 64 && a.head_dim != 128) || a.N != 2 * a.d_model)
         return hipErrorInvalidValue;
     constexpr int kLds = kStages * kStageBytes;

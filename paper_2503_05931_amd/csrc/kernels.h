@@ -33,7 +33,7 @@ struct GemmArgs {
     void* out;            // EPI_RESID: float [M,N] fragment order, += ; EPI_F32: float [M,N] row-major;
                           // EPI_RELU_T: T [M,N] fragment order; EPI_QKV: float q [M,d_model] row-major
     // EPI_QKV: columns [d,2d) and [2d,3d) go to the paged self-attention cache of this layer
-    void* k_pool;         // T [pages][H][16][Dh]
+    void* k_pool;         // T (or E4M3 codes, kv_fp8) [pages][H][16][Dh]
     void* v_pool;
     const int* page_table;  // [batch][max_pages]
     int max_pages;
@@ -58,6 +58,7 @@ struct GemmArgs {
     void* shadow_out;        // EPI_RESID_S: T [M,N] fragment order
     const void* shadow_g;    // EPI_RESID_S: T [N]
     int stat_tiles, m_stride;
+    int kv_fp8;              // EPI_QKV / EPI_CROSSKV: the caches hold 8-bit E4M3 codes instead of T
 };
 
 // Buffers in fragment order must hold a multiple of 128 rows (rows >= M are read, never written).
@@ -84,6 +85,7 @@ struct AttnArgs {
     void* out;            // T [B, d_model] in fragment order
     const void* K;        // self: T [pages][H][16][Dh]; cross: T [H][t_cap][Dh]  (this layer)
     const void* V;
+    int kv_fp8;           // K and V hold 8-bit E4M3 codes instead of T (bfloat16 mode only)
     const int* finished;  // [B]
     // self
     const int* page_table;

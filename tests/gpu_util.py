@@ -5,7 +5,11 @@ import numpy as np
 
 from paper_2503_05931_amd import binding, workloads as W
 
-TOL = {"fp32": 1e-4, "bf16": 3e-2}
+# "bf16+fp8kv": bf16 arithmetic with 8-bit key / value caches.  Both sides store the same codes except where the
+# kernels' bf16-level error moves a key or value element across the midpoint of two codes; such an element then
+# differs by a whole code step (6-12 % of its value), which on a few per cent of the elements amounts to about as
+# much as the storage rounding itself (which moves these tests' logits by 4-5e-2).
+TOL = {"fp32": 1e-4, "bf16": 3e-2, "bf16+fp8kv": 1e-1}
 
 
 def make_decoder(wl, max_batch=None, max_total=None, max_dec_len=None, poison=True, kv_pages=0, prefill_rows=0):
