@@ -147,6 +147,66 @@ def test_fp8_cache_greedy_with_eos(torch_cuda, oracle, prefill):
     dec.close()
 
 
+@pytest.mark.parametrize("name,sample,n_new", [
+    ("canary24_b64", [17, 63], 40),
+    ("flash4_b256", [0, 255], 40),
+    ("large24_b1024", [1023], 16),   # about 50 GB of caches; one page boundary
+])
+def test_fp8_cache_at_the_benchmark_sizes(torch_cuda, oracle, name, sample, n_new):
+    """The configurations bench.py --kv-fp8 times: sampled sequences teacher-forced against the oracle, then the
+    graph path at full length (every sequence emits max_new tokens; a second run is bit-identical)."""
+    import torch
+    from tests import gpu_util as G
+    from tests.test_gpu_full_size import _forced_check
+    wl = W.make(name)
+    wl.cfg.kv_fp8 = 1
+    dec, err, near = _forced_check(oracle, wl, sample, n_new, G.TOL["bf16+fp8kv"], max_dec_len=wl.cfg.max_dec_len)
+    print(f"{name} with fp8 caches, teacher-forced: max |dlogit| = {err:.3e}, near ties {near}")
+    if name != "large24_b1024":
+        B, P = len(wl.enc_lens), wl.cfg.prompt_len
+        dec.close()
+        dec = G.make_decoder(wl, prefill_rows=(P - 1) * ((B + 15) // 16 * 16))
+        dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+        prompt = torch.from_numpy(wl.prompt).to(dec.device)
+        t1, l1 = dec.aed_greedy_decode(prompt, wl.cfg.max_new)
+        t1, l1 = t1.cpu().numpy().copy(), l1.cpu().numpy().copy()
+        t2, l2 = dec.aed_greedy_decode(prompt, wl.cfg.max_new)
+        assert (l1 == wl.cfg.max_new).all() and (t1 == t2.cpu().numpy()).all() and (l1 == l2.cpu().numpy()).all()
+    dec.close()
+
+
+def test_fp8_cache_with_the_request_queue(torch_cuda, oracle):
+    """Slot refill writes the new requests' cross K/V through the frame map: with 8-bit caches too, every request's
+    tokens equal the oracle's up to its first near tie."""
+    import torch
+    from tests import gpu_util as G
+    rng = np.random.default_rng(5)
+    n_req, slots = 14, 4
+    enc_lens = rng.integers(3, 90, n_req).tolist()
+    wl = unit_workload("bf16", 256, 4, 64, enc_lens, seed=321, max_new=24, eos_id=3, kv_fp8=1)
+    cfg = wl.cfg
+    limits = rng.integers(1, 24, n_req).astype(np.int32)
+    m = oracle.Model(cfg, wl.weights)
+    ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, cfg.max_new, max_new_per_seq=limits,
+                                               want_logits=True)
+    dec = G.make_decoder(wl, max_batch=slots, max_total=int(np.sort(wl.enc_lens)[-slots:].sum()) + 64)
+    toks, lens, steps = dec.aed_greedy_decode_queue(dec.to_device(wl.enc), wl.enc_lens,
+                                                    torch.from_numpy(wl.prompt).to(dec.device), cfg.max_new, limits)
+    toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+    tol = G.TOL["bf16+fp8kv"]
+    whole = 0
+    for r in range(n_req):
+        n = int(ref_l[r])
+        first = int(G.first_near_tie(ref_logits[r:r + 1, :n], tol)[0])
+        assert (toks[r, :first] == ref_t[r, :first]).all(), f"request {r} forks before a near tie"
+        assert 1 <= lens[r] <= limits[r] and toks[r, lens[r] - 1] == cfg.eos_id and (toks[r, lens[r]:] == cfg.pad_id).all()
+        if first >= n:
+            whole += 1
+            assert lens[r] == n and (toks[r] == ref_t[r]).all()
+    print(f"queue with fp8 caches: {n_req} requests through {slots} slots in {steps} steps; {whole} requests fixed to the end")
+    dec.close()
+
+
 def test_fp8_cache_needs_bfloat16(torch_cuda):
     from paper_2503_05931_amd import binding
     from tests import gpu_util as G
