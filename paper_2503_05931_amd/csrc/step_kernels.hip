@@ -80,8 +80,20 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { retur
 __global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ logits, StateArgs st, int greedy,
                                                      int* __restrict__ step_out) {
     const int b = blockIdx.x, tid = threadIdx.x;
-    if (greedy && st.finished[b]) return;
+    // everything the decision needs is requested at once: the state words and this thread's share of the row
+    // (vocab is a multiple of 64: 4-vectors; up to four per thread in flight, then the rest of a long row)
+    const int fin = greedy ? st.finished[b] : 0;
     const int pos = st.seq_len[b];
+    const int n = greedy ? st.n_gen[b] : 0;
+    const int lim = greedy ? st.limit[b] : INT_MAX;
+    const float* row = logits + (size_t)b * st.vocab;
+    f32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid * 4 + u * 1024;
+        v[u] = i < st.vocab ? *reinterpret_cast<const f32x4*>(row + i) : f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    }
+    if (fin) return;
     if (greedy && pos + 1 < st.prompt_len) {  // still feeding the prompt: no token is emitted
         if (tid == 0) {
             st.cur_tok[b] = st.prompt[(size_t)b * st.prompt_stride + pos + 1];
@@ -89,12 +101,20 @@ __global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ l
         }
         return;
     }
-    const float* row = logits + (size_t)b * st.vocab;
     float bv = -INFINITY;
     int bi = INT_MAX;
-    for (int i = tid; i < st.vocab; i += 256) {
-        const float v = row[i];
-        if (better(v, i, bv, bi)) { bv = v; bi = i; }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = tid * 4 + u * 1024 + e;
+            if (i < st.vocab && better(v[u][e], i, bv, bi)) { bv = v[u][e]; bi = i; }
+        }
+    for (int base = tid * 4 + 4096; base < st.vocab; base += 1024) {
+        const f32x4 w = *reinterpret_cast<const f32x4*>(row + base);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (better(w[e], base + e, bv, bi)) { bv = w[e]; bi = base + e; }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -116,8 +136,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const float* __restrict__ l
         st.seq_len[b] = pos + 1;
         return;
     }
-    const int n = st.n_gen[b];
-    if (n + 1 >= st.limit[b]) tok = st.eos_id;  // forced end at the per-sequence target length
+    if (n + 1 >= lim) tok = st.eos_id;  // forced end at the per-sequence target length
     st.out_tokens[(size_t)b * st.out_stride + n] = tok;
     st.n_gen[b] = n + 1;
     st.cur_tok[b] = tok;
