@@ -415,10 +415,10 @@ template <typename T> static bool use_tiled(const GemmArgs& a) {
 }
 
 // The 256 x 256 direct-to-LDS kernel (cross K/V product only) needs whole 256-row tiles in A and enough
-// tiles to occupy most of the compute units with one workgroup each; its epilogue writes bfloat16 only.
+// tiles to occupy most of the compute units with one workgroup each.
 constexpr int kDmaMinTiles = 160;
 template <typename T> static bool use_dma_crosskv(const GemmArgs& a) {
-    return sizeof(T) == 2 && !a.kv_fp8 && a.N % 256 == 0 && a.N == 2 * a.d_model && a.K >= 256 &&
+    return sizeof(T) == 2 && a.N % 256 == 0 && a.N == 2 * a.d_model && a.K >= 256 &&
            a.a_rows >= (a.M + 255) / 256 * 256 && (long)((a.M + 255) / 256) * (a.N / 256) >= kDmaMinTiles;
 }
 

@@ -43,6 +43,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "gemm_common.h"
 #include "kernels.h"
 
 namespace aed {
@@ -65,6 +66,8 @@ __device__ __forceinline__ void wait_lds_barrier() { asm volatile("s_waitcnt lgk
 
 }  // namespace
 
+// FP8: the caches take 8-bit E4M3 codes (see store4_fp8) instead of bfloat16
+template <bool FP8>
 __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
     constexpr int S = kStages;
     extern __shared__ __align__(16) char lds[];
@@ -209,27 +212,57 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
         const int which = n_wave >= a.d_model;
         const int col = n_wave - (which ? a.d_model : 0);
         const int h = col / a.head_dim, e0 = col % a.head_dim;
-        bf16_t* __restrict__ dst = static_cast<bf16_t*>(which ? a.vc : a.kc) + (size_t)h * a.t_cap * a.head_dim + e0;
+        const size_t dst_off = (size_t)h * a.t_cap * a.head_dim + e0;
+        if constexpr (!FP8) {
+            bf16_t* __restrict__ dst = static_cast<bf16_t*>(which ? a.vc : a.kc) + dst_off;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
+            for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int c = 4 * nt + q;  // 16-byte chunk of the 128-byte row: columns 8 c + 4 hh .. + 3
-                    bf16x4 o;
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = 4 * nt + q;  // 16-byte chunk of the 128-byte row: columns 8 c + 4 hh .. + 3
+                        bf16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[mt][nt][4 * q + e];
-                    *reinterpret_cast<bf16x4*>(scr + r32 * 128 + ((c ^ (r32 & 7)) * 16) + hh * 8) = o;
+                        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[mt][nt][4 * q + e];
+                        *reinterpret_cast<bf16x4*>(scr + r32 * 128 + ((c ^ (r32 & 7)) * 16) + hh * 8) = o;
+                    }
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int row = p * 8 + (lane >> 3), c = lane & 7;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(scr + row * 128 + ((c ^ (row & 7)) * 16));
+                    const int m = tm * kBM + wm * 128 + mt * 32 + row;
+                    if (m < a.M) {
+                        const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
+                        *reinterpret_cast<f32x4*>(dst + frame * a.head_dim + c * 8) = v;
+                    }
                 }
+            }
+        } else {
+            // one byte per element: the wavefront's 32 x 64 block is 32 rows of 64 bytes = four 16-byte chunks
+            unsigned char* __restrict__ dst = static_cast<unsigned char*>(which ? a.vc : a.kc) + dst_off;
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int row = p * 8 + (lane >> 3), c = lane & 7;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(scr + row * 128 + ((c ^ (row & 7)) * 16));
-                const int m = tm * kBM + wm * 128 + mt * 32 + row;
-                if (m < a.M) {
-                    const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
-                    *reinterpret_cast<f32x4*>(dst + frame * a.head_dim + c * 8) = v;
+            for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        // columns 32 nt + 8 q + 4 hh .. + 3: chunk 2 nt + (q >> 1), byte 8 (q & 1) + 4 hh of it
+                        const int c = 2 * nt + (q >> 1);
+                        f32x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = acc[mt][nt][4 * q + e];
+                        store4_fp8(reinterpret_cast<unsigned char*>(scr) + r32 * 64 + ((c ^ (r32 & 3)) * 16) + (q & 1) * 8 + hh * 4, o);
+                    }
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    const int row = p * 16 + (lane >> 2), c = lane & 3;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(scr + row * 64 + ((c ^ (row & 3)) * 16));
+                    const int m = tm * kBM + wm * 128 + mt * 32 + row;
+                    if (m < a.M) {
+                        const size_t frame = a.out_row_map ? (size_t)a.out_row_map[m] : (size_t)m;
+                        *reinterpret_cast<f32x4*>(dst + frame * a.head_dim + c * 16) = v;
+                    }
                 }
             }
         }
@@ -238,23 +271,27 @@ __global__ __launch_bounds__(512) void gemm_dma_crosskv_kernel(GemmArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may land in LDS after the workgroup has ended
 }
 
-// bf16, EPI_CROSSKV.  A (fragment order) must hold whole 256-row tiles; N % 256 == 0; K % 64 == 0, K >= 256;
+// bf16 operands, EPI_CROSSKV (caches in bf16 or E4M3 codes).  A (fragment order) must hold whole 256-row tiles; N % 256 == 0; K % 64 == 0, K >= 256;
 // head_dim 64 or 128 and d_model a multiple of 64, so that a wavefront's 64 columns stay inside one head.
 hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s) {
-    if (a.M < 1 || a.N % kBN != 0 || a.K % 64 != 0 || a.K < 256 || a.d_model % 64 != 0 || a.kv_fp8 ||
+    if (a.M < 1 || a.N % kBN != 0 || a.K % 64 != 0 || a.K < 256 || a.d_model % 64 != 0 ||
         (a.head_dim != 64 && a.head_dim != 128) || a.N != 2 * a.d_model)
         return hipErrorInvalidValue;
     constexpr int kLds = kStages * kStageBytes;
     static bool configured = false;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     const int tiles = ((a.M + kBM - 1) / kBM) * (a.N / kBN);
     const int grid = tiles >= 256 ? 256 : (tiles + 7) / 8 * 8;  // one workgroup per CU, whole rounds over the XCDs
-    hipLaunchKernelGGL(gemm_dma_crosskv_kernel, dim3(grid), dim3(512), kLds, s, a);
+    if (a.kv_fp8) hipLaunchKernelGGL(gemm_dma_crosskv_kernel<true>, dim3(grid), dim3(512), kLds, s, a);
+    else hipLaunchKernelGGL(gemm_dma_crosskv_kernel<false>, dim3(grid), dim3(512), kLds, s, a);
     return hipGetLastError();
 }
 

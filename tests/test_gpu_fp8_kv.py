@@ -87,7 +87,7 @@ def test_fp8_cache_teacher_forced(torch_cuda, oracle, d_model, n_heads, head_dim
 
 @pytest.mark.parametrize("enc_lens", [
     [500, 500, 500, 500, 131],   # 272 tiles of 128 x 128: the tiled MFMA kernels write the codes
-    [700] * 7 + [411],           # enough for the 256 x 256 kernel, which writes bfloat16 only: must not be chosen
+    [700] * 7 + [411],           # enough for the persistent 256 x 256 kernel (ragged last row tile)
 ])
 def test_fp8_cache_large_cross_kv_precompute(torch_cuda, oracle, enc_lens):
     from tests import gpu_util as G

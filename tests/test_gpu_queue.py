@@ -19,13 +19,13 @@ def torch_cuda():
 
 
 def queue_workload(dtype, n_req, seed, max_new, d_model=256, n_heads=4, head_dim=64, max_enc=130, eos_id=-1, pad_id=0,
-                   min_enc=1):
+                   min_enc=1, kv_fp8=0):
     rng = np.random.default_rng(seed)
     enc_lens = rng.integers(min_enc, max_enc + 1, size=n_req)
     enc_lens[rng.integers(0, n_req)] = max_enc          # the longest length occurs
     cfg = W.DecoderConfig(name="queue", n_layers=2, d_model=d_model, n_heads=n_heads, head_dim=head_dim, d_ffn=512,
                           vocab=256, dtype=dtype, batch=n_req, prompt_len=3, max_new=max_new, eos_id=eos_id,
-                          pad_id=pad_id)
+                          pad_id=pad_id, kv_fp8=kv_fp8)
     return W.custom(cfg, enc_lens, seed, random_ln=True)
 
 
@@ -39,7 +39,7 @@ def pick_eos(oracle, dtype, n_req, seed, max_new, **kw):
 
 def run_queue_case(torch, oracle, dtype, n_req, slots, seed, max_new, frames_cap=None, **kw):
     from tests import gpu_util as G
-    tol = G.TOL[dtype]
+    tol = G.TOL["bf16+fp8kv" if kw.get("kv_fp8") else dtype]
     eos = pick_eos(oracle, dtype, n_req, seed, max_new, **kw)
     wl = queue_workload(dtype, n_req, seed, max_new, eos_id=eos, pad_id=5, **kw)
     rng = np.random.default_rng(seed + 1)
@@ -96,6 +96,12 @@ def test_queue_large_refill_through_the_frame_map(torch_cuda, oracle):
     # through the 256 x 256 direct-to-LDS kernel and its frame map
     run_queue_case(torch_cuda, oracle, "bf16", n_req=36, slots=26, seed=29, max_new=8, d_model=1024, n_heads=8,
                    head_dim=128, max_enc=300, min_enc=200)
+
+
+def test_queue_large_refill_with_fp8_caches(torch_cuda, oracle):
+    # the same refill size with 8-bit caches: the 256 x 256 kernel writes E4M3 codes through the frame map
+    run_queue_case(torch_cuda, oracle, "bf16", n_req=36, slots=26, seed=31, max_new=8, d_model=1024, n_heads=8,
+                   head_dim=128, max_enc=300, min_enc=200, kv_fp8=1)
 
 
 def test_queue_fewer_requests_than_slots_and_errors(torch_cuda, oracle):
