@@ -85,13 +85,15 @@ def test_fp8_cache_teacher_forced(torch_cuda, oracle, d_model, n_heads, head_dim
     dec.close()
 
 
-@pytest.mark.parametrize("enc_lens", [
-    [500, 500, 500, 500, 131],   # 272 tiles of 128 x 128: the tiled MFMA kernels write the codes
-    [700] * 7 + [411],           # enough for the persistent 256 x 256 kernel (ragged last row tile)
+@pytest.mark.parametrize("d_model,n_heads,head_dim,enc_lens", [
+    (1024, 8, 128, [500, 500, 500, 500, 131]),   # 272 tiles of 128 x 128: the tiled MFMA kernels write the codes
+    (1024, 8, 128, [700] * 7 + [411]),           # enough for the persistent 256 x 256 kernel (ragged last row tile)
+    (512, 8, 64, [1300] * 7 + [1150]),           # the same kernel, one head per wavefront's 64 columns
 ])
-def test_fp8_cache_large_cross_kv_precompute(torch_cuda, oracle, enc_lens):
+def test_fp8_cache_large_cross_kv_precompute(torch_cuda, oracle, d_model, n_heads, head_dim, enc_lens):
     from tests import gpu_util as G
-    wl = unit_workload("bf16", 1024, 8, 128, enc_lens, seed=95, n_layers=1, d_ffn=256, vocab=64, max_new=8, kv_fp8=1)
+    wl = unit_workload("bf16", d_model, n_heads, head_dim, enc_lens, seed=95, n_layers=1, d_ffn=256, vocab=64,
+                       max_new=8, kv_fp8=1)
     m = oracle.Model(wl.cfg, wl.weights)
     B = len(enc_lens)
     toks = random_tokens(wl.cfg, B, 4, 8)
