@@ -47,6 +47,10 @@ def test_workspace_bytes_counts_the_caches(lib):
     weights = (L * 16 * d * d + 4096 * d) * e         # the library's re-ordered copy of every matrix
     enc_copy = 64 * 500 * d * e                       # the batch's encoder frames in fragment order
     assert cross + self_kv + weights + enc_copy < n < cross + self_kv + weights + enc_copy + (64 << 20)
+    # 8-bit caches: one byte per cached key / value element, everything else unchanged
+    c.kv_fp8 = 1
+    n8 = binding.aed_workspace_bytes(c)
+    assert abs((n - n8) - (cross + self_kv) // 2) < (1 << 20)
 
 
 @pytest.mark.parametrize("field,value,status", [
@@ -57,6 +61,8 @@ def test_workspace_bytes_counts_the_caches(lib):
     ("max_batch", 0, binding.AED_EINVAL),
     ("eos_id", 4096, binding.AED_EINVAL),
     ("kv_pages", -1, binding.AED_EINVAL),
+    ("kv_fp8", 2, binding.AED_EINVAL),
+    ("prefill_rows", -1, binding.AED_EINVAL),
     ("norm_type", 1, binding.AED_EUNSUPPORTED),
     ("page_size", 32, binding.AED_EUNSUPPORTED),
     ("d_ffn", 1000, binding.AED_EUNSUPPORTED),
@@ -69,6 +75,24 @@ def test_bad_configs_are_rejected(lib, field, value, status):
         binding.aed_workspace_bytes(c)
     assert ei.value.status == status
     assert len(str(ei.value)) > 10
+
+
+def test_fp8_caches_need_bfloat16(lib):
+    c = good_config()
+    c.dtype, c.kv_fp8 = 0, 1
+    with pytest.raises(binding.AedError) as ei:
+        binding.aed_workspace_bytes(c)
+    assert ei.value.status == binding.AED_EUNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
 def test_unsupported_head_dim(lib):
