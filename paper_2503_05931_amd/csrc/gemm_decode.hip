@@ -88,6 +88,37 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             e_res[j] = live ? *reinterpret_cast<const f32x4*>(static_cast<const char*>(a.out) + frag_elem_off<4>(m, n, a.N))
                             : zero;
     }
+    // EPI_QKV: where this thread's key / value columns go in the paged cache (element index, -1: nowhere).  The
+    // sequence's state and its page-table entry are two dependent loads; fetched here, they are off the critical
+    // path at the end.
+    long long e_kv[EP];
+    if constexpr (EPI == EPI_QKV) {
+#pragma unroll
+        for (int j = 0; j < EP; ++j) {
+            const int idx = tid + 256 * j;
+            const int t = idx >> 6, l = idx & 63;
+            const int m = m0 + (t / NT) * 16 + (l & 15);
+            const int n = n0 + (t % NT) * 16 + (l >> 4) * 4;
+            e_kv[j] = -1;
+            if (idx < MT * NT * 64 && m < M && n >= a.d_model && !a.finished[m]) {
+                const int c = n - (n >= 2 * a.d_model ? 2 * a.d_model : a.d_model);
+                const int h = c / a.head_dim, e = c % a.head_dim;
+                const int pos = a.seq_len[m];
+                const int page = a.page_table[(size_t)m * a.max_pages + (pos >> 4)];
+                e_kv[j] = (((long long)page * a.n_heads + h) * kPage + (pos & 15)) * a.head_dim + e;
+            }
+        }
+    }
+    // the epilogue of EPI_QKV with the cache position already known
+    auto store_qkv = [&](int m, int n, f32x4 s, long long at) {
+        if (n < a.d_model) {
+            store4(static_cast<float*>(a.out) + (size_t)m * a.d_model + n, s);
+        } else if (at >= 0) {
+            void* pool = n >= 2 * a.d_model ? a.v_pool : a.k_pool;
+            if (a.kv_fp8) store4_fp8(static_cast<unsigned char*>(pool) + at, s);
+            else store4(static_cast<T*>(pool) + at, s);
+        }
+    };
     float stat_n = 0.f;  // elements behind each of the four partial results of the row statistics
     // mean and sum of squared deviations of local row rl over all columns, from the four partial results
     auto row_stats = [&](int rl, float& mu, float& m2) {
@@ -275,7 +306,8 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             row_stats(mt * 16 + (l & 15), mu, m2);
             const float rstd = 1.0f / sqrtf(m2 / (float)K + a.ln_eps), shift = mu - e_mu[j];
             s = (s - shift * e_aux[j]) * rstd + e_bias[j];
-            gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
+            if constexpr (EPI == EPI_QKV) store_qkv(m, n, s, e_kv[j]);
+            else gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
             if (n == 0) a.mu_hat_out[m] = mu;  // the next residual update shifts its shadow by this
         } else if constexpr (RS) {
             const float mu_old = e_mu[j];
@@ -297,7 +329,8 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             }
         } else {
             s += e_bias[j];
-            gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
+            if constexpr (EPI == EPI_QKV) store_qkv(m, n, s, e_kv[j]);
+            else gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
         }
     }
 }
