@@ -201,7 +201,9 @@ int64_t aed_layer_matrix_params(const aed_config *cfg);
 /* ---- inspection and measurement (used by the tests and the benchmark) ---- */
 
 /* Copy one sequence's cross-attention K and V of one layer to HOST float32
- * buffers [enc_len, d_model] (synchronises). */
+ * buffers [enc_len, d_model] (synchronises).  The values are what the cache
+ * holds: rounded to dtype, or to E4M3 with kv_fp8 (every value returned is
+ * then exactly the value of its code). */
 aed_status aed_read_cross_kv(aed_decoder *dec, int32_t layer, int32_t seq,
                              float *k_out, float *v_out);
 
