@@ -132,6 +132,10 @@ void make_layout(const aed_config* c, Layout* L) {
     L->total = off;
 }
 
+// The memory-side cache holds 256 MB; a decoder whose per-step weights stay well below that keeps them there from
+// one step to the next (the keys and values are streamed around the caches), a larger one cannot.
+constexpr double kCacheResidentWeightBytes = 192e6;
+
 struct GraphKey {
     int batch = -1, n_items = 0, self_chunk = 0, self_nchunks = 0, prompt_len = 0, max_new = 0;
     long long total_enc = 0;
@@ -148,6 +152,7 @@ struct aed_decoder {
     Dtype dt;
     size_t esz;
     size_t kv_esz;  // bytes per cached key / value element: esz, or 1 for E4M3 codes
+    int w_nt = 0;   // the decode step's weights do not fit the memory-side cache: stream them with the non-temporal hint
     Layout lay;
     std::vector<aed_layer_weights> layers;  // caller's pointers (biases, LayerNorm, embeddings are used in place)
     aed_weights w;
@@ -254,6 +259,7 @@ GemmArgs gemm_base(const aed_decoder* d) {
     g.head_dim = d->cfg.head_dim;
     g.d_model = d->cfg.d_model;
     g.kv_fp8 = d->cfg.kv_fp8;
+    g.w_nt = d->w_nt;
     return g;
 }
 
@@ -693,6 +699,10 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
     d->dt = cfg->dtype == 1 ? kBF16 : kF32;
     d->esz = cfg->dtype == 1 ? 2 : 4;
     d->kv_esz = cfg->kv_fp8 ? 1 : d->esz;
+    {   // weights a decode step streams: 14 d^2 + ... per layer (all but the cross K/V matrices) and the vocabulary matrix
+        const double dm = cfg->d_model, step_w = ((double)cfg->n_layers * (6 * dm * dm + 2 * dm * cfg->d_ffn) + dm * cfg->vocab) * d->esz;
+        d->w_nt = step_w > kCacheResidentWeightBytes;
+    }
     d->lay = L;
     d->layers.assign(weights->layers, weights->layers + cfg->n_layers);
     d->w = *weights;

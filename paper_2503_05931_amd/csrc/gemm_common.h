@@ -19,6 +19,13 @@ __device__ __forceinline__ Frag16<bf16_t> load_frag(const bf16_t* blk, int lane)
     f.hi = p[64];
     return f;
 }
+__device__ __forceinline__ Frag16<bf16_t> load_frag_nt(const bf16_t* blk, int lane) {
+    Frag16<bf16_t> f;
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(blk) + lane;
+    f.lo = __builtin_nontemporal_load(p);
+    f.hi = __builtin_nontemporal_load(p + 64);
+    return f;
+}
 __device__ __forceinline__ Frag16<float> load_frag(const float* blk, int lane) {
     Frag16<float> f;
     const f32x4* p = reinterpret_cast<const f32x4*>(blk) + lane;
@@ -29,6 +36,7 @@ __device__ __forceinline__ Frag16<float> load_frag(const float* blk, int lane) {
     }
     return f;
 }
+__device__ __forceinline__ Frag16<float> load_frag_nt(const float* blk, int lane) { return load_frag(blk, lane); }
 __device__ __forceinline__ void store_frag(bf16_t* blk, int lane, const Frag16<bf16_t>& f) {
     bf16x8* p = reinterpret_cast<bf16x8*>(blk) + lane;
     p[0] = f.lo;

@@ -34,7 +34,8 @@ namespace aed {
 constexpr int kMaxLnBlocks = 4;  // PRO_LN: K <= 4 waves * 4 blocks * 64 = 1024
 constexpr int kMaxStatTilesPerGroup = 16;  // folded LayerNorm: d_model <= 1024 = 4 groups * 16 tiles * 16 columns
 
-template <typename T, int PRO, int EPI, int MT, int NT>
+// WNT: W is loaded with the non-temporal hint (GemmArgs::w_nt)
+template <typename T, int PRO, int EPI, int MT, int NT, bool WNT>
 __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
     constexpr int BM = 16 * MT, BN = 16 * NT;
     constexpr int EP = (MT * NT * 64 + 255) / 256;  // output 4-vectors per thread in the epilogue
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         for (int i = 0; i < kMaxLnBlocks; ++i)
             if (i < nblk)
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) wf[nt][i] = load_frag(wblk(nt, i), lane);
+                for (int nt = 0; nt < NT; ++nt) wf[nt][i] = WNT ? load_frag_nt(wblk(nt, i), lane) : load_frag(wblk(nt, i), lane);
         // LayerNorm gain/shift for this lane's k values, fetched before the statistics are known
         const T* __restrict__ G = static_cast<const T*>(a.ln_g);
         const T* __restrict__ Bt = static_cast<const T*>(a.ln_b);
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
                 const int i = blk0 + u;
                 if (i < nblk) {
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) wf[buf][u][nt] = load_frag(wblk(nt, i), lane);
+                    for (int nt = 0; nt < NT; ++nt) wf[buf][u][nt] = WNT ? load_frag_nt(wblk(nt, i), lane) : load_frag(wblk(nt, i), lane);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
                         af[buf][u][mt] = load_frag(
@@ -395,10 +396,13 @@ __global__ __launch_bounds__(256) void layernorm_frag_kernel(const char* __restr
     store_frag(reinterpret_cast<T*>(Hout + frag_block_off<ES>(row >> 4, kb, K)), frag_lane, f);
 }
 
+constexpr int kWntMaxM = 128;
 template <typename T, int PRO, int EPI, int MT, int NT>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     dim3 grid(a.N / (16 * NT), (a.M + 16 * MT - 1) / (16 * MT));
-    hipLaunchKernelGGL((gemm_decode_kernel<T, PRO, EPI, MT, NT>), grid, dim3(256), 0, s, a);
+    // the hint only where few row tiles share W: with many (measured at M = 1024) they need it from the cache
+    if (a.w_nt && a.M <= kWntMaxM) hipLaunchKernelGGL((gemm_decode_kernel<T, PRO, EPI, MT, NT, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((gemm_decode_kernel<T, PRO, EPI, MT, NT, false>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

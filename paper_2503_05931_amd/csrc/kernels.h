@@ -59,6 +59,8 @@ struct GemmArgs {
     const void* shadow_g;    // EPI_RESID_S: T [N]
     int stat_tiles, m_stride;
     int kv_fp8;              // EPI_QKV / EPI_CROSSKV: the caches hold 8-bit E4M3 codes instead of T
+    int w_nt;                // streaming kernel: load W with the non-temporal hint (weights that are not expected to
+                             // survive in the caches until the next step anyway, and should not push other data out)
 };
 
 // Buffers in fragment order must hold a multiple of 128 rows (rows >= M are read, never written).
