@@ -135,6 +135,10 @@ void make_layout(const aed_config* c, Layout* L) {
 // The memory-side cache holds 256 MB; a decoder whose per-step weights stay well below that keeps them there from
 // one step to the next (the keys and values are streamed around the caches), a larger one cannot.
 constexpr double kCacheResidentWeightBytes = 192e6;
+// Of a larger decoder, the first layers whose weights add up to this much are loaded the ordinary way and so stay
+// cached from step to step; the rest is streamed with the non-temporal hint.  (24 layers of 29.4 MB: 7 or 8 resident
+// layers are the optimum, 1.195 -> 1.160 ms per step; from 9 on the cache thrashes and the gain is gone.)
+constexpr double kResidentLayerBytes = 220e6;
 
 struct GraphKey {
     int batch = -1, n_items = 0, self_chunk = 0, self_nchunks = 0, prompt_len = 0, max_new = 0;
@@ -152,7 +156,8 @@ struct aed_decoder {
     Dtype dt;
     size_t esz;
     size_t kv_esz;  // bytes per cached key / value element: esz, or 1 for E4M3 codes
-    int w_nt = 0;   // the decode step's weights do not fit the memory-side cache: stream them with the non-temporal hint
+    int w_nt = 0;   // the decode step's weights do not fit the memory-side cache: stream them with the non-temporal hint,
+    int resident_layers = 0;  // except those of the first resident_layers layers
     Layout lay;
     std::vector<aed_layer_weights> layers;  // caller's pointers (biases, LayerNorm, embeddings are used in place)
     aed_weights w;
@@ -249,7 +254,8 @@ int pick_chunk(long long total_keys, int max_len, int batch, int n_heads) {
 }
 
 // ---------------------------------------------------------------- kernel argument builders
-GemmArgs gemm_base(const aed_decoder* d) {
+// layer: whose weights the product reads (n_layers: the vocabulary matrix)
+GemmArgs gemm_base(const aed_decoder* d, int layer) {
     GemmArgs g;
     memset(&g, 0, sizeof g);
     g.ln_eps = d->cfg.ln_eps;
@@ -259,7 +265,7 @@ GemmArgs gemm_base(const aed_decoder* d) {
     g.head_dim = d->cfg.head_dim;
     g.d_model = d->cfg.d_model;
     g.kv_fp8 = d->cfg.kv_fp8;
-    g.w_nt = d->w_nt;
+    g.w_nt = d->w_nt && layer >= d->resident_layers;
     return g;
 }
 
@@ -286,7 +292,7 @@ void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float
 
 hipError_t k_ln_qkv(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
-    GemmArgs g = gemm_base(d);
+    GemmArgs g = gemm_base(d, l);
     g.A = d->at<float>(d->lay.x);
     g.W = d->fw[l].w_qkv; g.bias = w.b_qkv; g.ln_g = w.ln1_g; g.ln_b = w.ln1_b;
     g.N = 3 * d->cfg.d_model; g.K = d->cfg.d_model;
@@ -334,8 +340,8 @@ hipError_t k_self_attn(aed_decoder* d, int l) {
 }
 
 // x += A . W^T + bias; next_g: gain of the LayerNorm that reads x next (its shadow is written with it)
-hipError_t k_resid(aed_decoder* d, const void* A, const void* W, const void* bias, int K, const void* next_g) {
-    GemmArgs g = gemm_base(d);
+hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const void* bias, int K, const void* next_g) {
+    GemmArgs g = gemm_base(d, l);
     g.A = A; g.W = W; g.bias = bias;
     g.N = d->cfg.d_model; g.K = K;
     g.out = d->at<float>(d->lay.x);
@@ -354,7 +360,7 @@ hipError_t k_resid(aed_decoder* d, const void* A, const void* W, const void* bia
 
 hipError_t k_ln_crossq(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
-    GemmArgs g = gemm_base(d);
+    GemmArgs g = gemm_base(d, l);
     g.A = d->at<float>(d->lay.x);
     g.W = d->fw[l].w_cq; g.bias = w.b_cq; g.ln_g = w.ln2_g; g.ln_b = w.ln2_b;
     g.N = d->cfg.d_model; g.K = d->cfg.d_model;
@@ -380,7 +386,7 @@ hipError_t k_cross_attn(aed_decoder* d, int l) {
 
 hipError_t k_ln_ffn1(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
-    GemmArgs g = gemm_base(d);
+    GemmArgs g = gemm_base(d, l);
     g.A = d->at<float>(d->lay.x);
     g.W = d->fw[l].w_ff1; g.bias = w.b_ff1; g.ln_g = w.ln3_g; g.ln_b = w.ln3_b;
     g.N = d->cfg.d_ffn; g.K = d->cfg.d_model;
@@ -393,7 +399,7 @@ hipError_t k_ln_ffn1(aed_decoder* d, int l) {
 }
 
 hipError_t k_ln_vocab(aed_decoder* d) {
-    GemmArgs g = gemm_base(d);
+    GemmArgs g = gemm_base(d, d->cfg.n_layers);
     g.A = d->at<float>(d->lay.x);
     g.W = d->fw_out; g.bias = d->w.b_out; g.ln_g = d->w.lnf_g; g.ln_b = d->w.lnf_b;
     g.N = d->cfg.vocab; g.K = d->cfg.d_model;
@@ -409,7 +415,7 @@ hipError_t k_ln_vocab(aed_decoder* d) {
 // each row, else row m is frame m.
 hipError_t k_cross_kv(aed_decoder* d, int l, long long rows, const int* frame_map) {
     const aed_layer_weights& w = d->layers[l];
-    GemmArgs g = gemm_base(d);
+    GemmArgs g = gemm_base(d, l);
     g.A = d->ws + d->lay.enc_frag;
     g.W = d->fw[l].w_ckv; g.bias = w.b_ckv;
     g.out_row_map = frame_map;
@@ -426,13 +432,13 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
     switch (cls) {
         case AED_K_LN_QKV: return k_ln_qkv(d, l);
         case AED_K_SELF_ATTN: return k_self_attn(d, l);
-        case AED_K_SELF_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model, w.ln2_g);
+        case AED_K_SELF_OUT: return k_resid(d, l, d->ws + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model, w.ln2_g);
         case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
         case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
-        case AED_K_CROSS_OUT: return k_resid(d, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model, w.ln3_g);
+        case AED_K_CROSS_OUT: return k_resid(d, l, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model, w.ln3_g);
         case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
         case AED_K_FFN2:
-            return k_resid(d, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn,
+            return k_resid(d, l, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn,
                            l + 1 < d->cfg.n_layers ? d->layers[l + 1].ln1_g : d->w.lnf_g);
         case AED_K_CROSS_KV: return k_cross_kv(d, l, d->total_enc, nullptr);
         default: return hipErrorInvalidValue;
@@ -702,6 +708,8 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
     {   // weights a decode step streams: 14 d^2 + ... per layer (all but the cross K/V matrices) and the vocabulary matrix
         const double dm = cfg->d_model, step_w = ((double)cfg->n_layers * (6 * dm * dm + 2 * dm * cfg->d_ffn) + dm * cfg->vocab) * d->esz;
         d->w_nt = step_w > kCacheResidentWeightBytes;
+        const double layer_w = (6 * dm * dm + 2 * dm * cfg->d_ffn) * d->esz;
+        d->resident_layers = d->w_nt ? std::min(cfg->n_layers, (int)(kResidentLayerBytes / layer_w)) : 0;
     }
     d->lay = L;
     d->layers.assign(weights->layers, weights->layers + cfg->n_layers);
