@@ -394,3 +394,32 @@ def test_degenerate_shapes_and_reuse(torch_cuda, oracle):
     glog, gids = G.forced_logits_gpu(dec, wl1, tk)
     G.check_forced(ref, glog, gids, tol)
     dec.close()
+
+
+def test_same_shape_other_lengths_on_one_decoder(torch_cuda, oracle):
+    """Two batches on one decoder with the same batch size, the same number of work items and the same total of
+    encoder frames, but the lengths in another order: the launch graphs recorded for the first batch are replayed for
+    the second (their shape is the same) and must find the second batch's work list and offsets."""
+    from tests import gpu_util as G
+    torch = torch_cuda
+    lens_a, lens_b = [90, 20, 55, 7], [20, 7, 90, 55]
+    wl_a = unit_workload("bf16", 256, 4, 64, lens_a, seed=61, max_new=12)
+    wl_b = unit_workload("bf16", 256, 4, 64, lens_b, seed=61, max_new=12)   # same weights (same seed and shapes)
+    for k in ("tok_emb", "w_out"):
+        assert np.array_equal(wl_a.weights[k], wl_b.weights[k])
+    dec = G.make_decoder(wl_a)
+    for wl in (wl_a, wl_b, wl_a):
+        m = oracle.Model(wl.cfg, wl.weights)
+        ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, 12, want_logits=True)
+        dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+        toks, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), 12)
+        toks = toks.cpu().numpy()
+        first = G.first_near_tie(ref_logits, G.TOL["bf16"])
+        for b in range(4):
+            assert (toks[b, :first[b]] == ref_t[b, :first[b]]).all(), f"sequence {b} forks before a near tie"
+        # and teacher-forced through the step path (its own recorded graph), every logit
+        forced = np.concatenate([wl.prompt, ref_t[:, :-1]], axis=1)
+        glog, gids = G.forced_logits_gpu(dec, wl, forced)
+        P = wl.cfg.prompt_len
+        G.check_forced(ref_logits, glog[:, P - 1:], gids[:, P - 1:], G.TOL["bf16"])
+    dec.close()
