@@ -97,7 +97,8 @@ typedef struct aed_weights {
  * Errors: AED_EINVAL (NULL, struct_size mismatch, non-positive or inconsistent
  * dimensions, n_heads*head_dim != d_model), AED_EUNSUPPORTED (shape without a
  * kernel: head_dim not 64/128, d_model not a multiple of 256 or above 1024,
- * d_ffn or vocab not a multiple of 64, page_size != 16, norm_type != 0). */
+ * d_ffn not a multiple of 256, vocab not a multiple of 64, page_size != 16,
+ * norm_type != 0). */
 aed_status aed_workspace_bytes(const aed_config *cfg, size_t *bytes);
 
 /* Create a decoder.  workspace: DEVICE memory, 256-byte aligned, at least
@@ -212,6 +213,12 @@ aed_status aed_read_cross_kv(aed_decoder *dec, int32_t layer, int32_t seq,
  * (synchronises).  Buffers must hold max_dec_len rows. */
 aed_status aed_read_self_kv(aed_decoder *dec, int32_t layer, int32_t seq,
                             float *k_out, float *v_out, int32_t *n_positions);
+
+/* Copy the logits of the most recent decoder step (aed_decode_step, or the
+ * last step aed_greedy_decode ran) to a HOST float32 buffer [batch, vocab]
+ * (synchronises).  Rows of sequences that had finished before that step hold
+ * unspecified values. */
+aed_status aed_read_logits(aed_decoder *dec, float *logits_out);
 
 /* Kernel classes of one decoder step, for aed_time_kernels. */
 enum {

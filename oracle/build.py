@@ -13,7 +13,7 @@ def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(
             os.path.getmtime(src), os.path.getmtime(os.path.join(HERE, "aed_oracle.h"))):
         return LIB
-    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+    cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
            "-o", LIB, src, "-lm"]
     subprocess.run(cmd, check=True, cwd=HERE)
     return LIB

@@ -28,7 +28,7 @@ KERNEL_NAMES = ["ln_qkv", "self_attn", "self_out", "ln_crossq", "cross_attn", "c
 EXPORTS = ("aed_workspace_bytes", "aed_decoder_create", "aed_decoder_destroy", "aed_cross_kv_precompute",
            "aed_cross_kv_precompute_padded", "aed_decode_step", "aed_greedy_decode", "aed_greedy_decode_queue",
            "aed_last_error",
-           "aed_layer_matrix_params", "aed_read_cross_kv", "aed_read_self_kv", "aed_time_kernels",
+           "aed_layer_matrix_params", "aed_read_cross_kv", "aed_read_self_kv", "aed_read_logits", "aed_time_kernels",
            "aed_kernel_work")
 
 
@@ -81,6 +81,7 @@ def load():
     lib.aed_layer_matrix_params.restype = C.c_int64
     lib.aed_read_cross_kv.argtypes = [vp, C.c_int32, C.c_int32, f32p, f32p]
     lib.aed_read_self_kv.argtypes = [vp, C.c_int32, C.c_int32, f32p, f32p, i32p]
+    lib.aed_read_logits.argtypes = [vp, f32p]
     lib.aed_time_kernels.argtypes = [vp, C.c_int32, C.c_int32, f32p, i32p]
     lib.aed_kernel_work.argtypes = [vp, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     for n in EXPORTS:
@@ -277,6 +278,12 @@ class Decoder:
         self._check(self.lib.aed_read_self_kv(self.handle, layer, seq, k.ctypes.data_as(fp), v.ctypes.data_as(fp),
                                               C.byref(n)))
         return k[:n.value], v[:n.value]
+
+    def aed_read_logits(self):
+        """Logits [batch, vocab] of the most recent decoder step (host float32)."""
+        out = np.zeros((self.batch, self.cfg.vocab), np.float32)
+        self._check(self.lib.aed_read_logits(self.handle, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
 
     def aed_time_kernels(self, kernel_class: int, reps: int):
         ms, n = C.c_float(0), C.c_int32(0)

@@ -519,6 +519,9 @@ aed_status start_batch(aed_decoder* d, const void* enc, bool padded, int t_max, 
                      [](const int4& p, const int4& q) { return (p.z & 0xFFFF) > (q.z & 0xFFFF); });
 
     HIP_TRY(d, hipStreamSynchronize(d->stream));  // the previous batch's work is done with the old tables
+    // the chunk merge's arrival counters return to zero by themselves after every launch; a batch still starts
+    // from zero, whatever an earlier launch that ended abnormally may have left
+    HIP_TRY(d, hipMemsetAsync(d->ws + d->lay.counters, 0, (size_t)d->lay.act_rows * d->cfg.n_heads * 4, d->stream));
     HIP_TRY(d, hipMemcpyAsync(d->at<int>(d->lay.enc_off), off.data(), off.size() * 4, hipMemcpyHostToDevice, d->stream));
     HIP_TRY(d, hipMemcpyAsync(d->at<int4>(d->lay.items), items.data(), items.size() * 16, hipMemcpyHostToDevice, d->stream));
     if (padded) {
@@ -1004,6 +1007,7 @@ extern "C" aed_status aed_greedy_decode_queue(aed_decoder* d, const void* enc_st
     // Slot b owns pages [b * need_pages, (b + 1) * need_pages) for the whole run: a refilled slot starts again at
     // position 0 and overwrites them.  Frames of the cross K/V cache are handed out per request.
     HIP_TRY(d, hipStreamSynchronize(d->stream));
+    HIP_TRY(d, hipMemsetAsync(d->ws + d->lay.counters, 0, (size_t)d->lay.act_rows * d->cfg.n_heads * 4, d->stream));
     d->state = aed_decoder::NO_BATCH;  // the per-batch inspection calls do not apply to a queue run
     d->batch = B;
     d->n_items = B;  // one work item per slot (whole sequences), so that the captured launch shape never changes
@@ -1215,6 +1219,15 @@ aed_status aed_read_self_kv(aed_decoder* d, int32_t layer, int32_t seq, float* k
             }
         }
     }
+    return AED_OK;
+}
+
+aed_status aed_read_logits(aed_decoder* d, float* logits_out) {
+    if (!d) return AED_EINVAL;
+    if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
+    if (!logits_out) return fail(d, AED_EINVAL, "logits_out is NULL");
+    HIP_TRY(d, hipStreamSynchronize(d->stream));
+    HIP_TRY(d, hipMemcpy(logits_out, d->at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4, hipMemcpyDeviceToHost));
     return AED_OK;
 }
 

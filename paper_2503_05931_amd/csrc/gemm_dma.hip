@@ -45,6 +45,7 @@
 #include "common.h"
 #include "gemm_common.h"
 #include "kernels.h"
+#include "device_once.h"
 
 namespace aed {
 
@@ -278,16 +279,15 @@ hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s) {
         (a.head_dim != 64 && a.head_dim != 128) || a.N != 2 * a.d_model)
         return hipErrorInvalidValue;
     constexpr int kLds = kStages * kStageBytes;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static DeviceOnce configured;
+    hipError_t e = configured.run([&]() {
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel<false>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+        if (e1 != hipSuccess) return e1;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_crosskv_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    });
+    if (e != hipSuccess) return e;
     const int tiles = ((a.M + kBM - 1) / kBM) * (a.N / kBN);
     const int grid = tiles >= 256 ? 256 : (tiles + 7) / 8 * 8;  // one workgroup per CU, whole rounds over the XCDs
     if (a.kv_fp8) hipLaunchKernelGGL(gemm_dma_crosskv_kernel<true>, dim3(grid), dim3(512), kLds, s, a);

@@ -23,6 +23,7 @@
 #include "common.h"
 #include "gemm_common.h"
 #include "kernels.h"
+#include "device_once.h"
 
 namespace aed {
 
@@ -246,13 +247,12 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
 template <int EPI, bool LNS>
 static hipError_t launch_dma128_one(const GemmArgs& a, hipStream_t s) {
     constexpr int kLds = kStages * kStageBytes;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma128_kernel<EPI, LNS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static DeviceOnce configured;
+    hipError_t e = configured.run([&]() {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma128_kernel<EPI, LNS>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    });
+    if (e != hipSuccess) return e;
     const int tiles = ((a.M + kBM - 1) / kBM) * (a.N / kBN);
     const int grid = tiles >= 256 ? 256 : (tiles + 7) / 8 * 8;  // at most one workgroup per CU, whole rounds over the XCDs
     hipLaunchKernelGGL((gemm_dma128_kernel<EPI, LNS>), dim3(grid), dim3(256), kLds, s, a);

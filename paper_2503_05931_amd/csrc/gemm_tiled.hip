@@ -22,6 +22,7 @@
 #include "common.h"
 #include "gemm_common.h"
 #include "kernels.h"
+#include "device_once.h"
 
 namespace aed {
 
@@ -196,13 +197,12 @@ template <int EPI, int WM, int WN, int D, bool LNS>
 static hipError_t launch_tiled_one(const GemmArgs& a, hipStream_t s) {
     constexpr int BM = 32 * WM, BN = 32 * WN;
     constexpr size_t kLds = 2ull * (BM / 16 + BN / 16) * 2048;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<EPI, WM, WN, D, LNS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static DeviceOnce configured;
+    hipError_t e = configured.run([&]() {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<EPI, WM, WN, D, LNS>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+    });
+    if (e != hipSuccess) return e;
     const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
     const int grid = (tiles + 7) / 8 * 8;  // whole rounds over the 8 XCDs (surplus ids exit at once)
     hipLaunchKernelGGL((gemm_tiled_kernel<EPI, WM, WN, D, LNS>), dim3(grid), dim3(256), kLds, s, a);

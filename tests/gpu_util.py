@@ -25,17 +25,19 @@ def make_decoder(wl, max_batch=None, max_total=None, max_dec_len=None, poison=Tr
     return dec
 
 
-def forced_logits_gpu(dec, wl, tokens):
-    """Teacher-forced run through aed_decode_step: tokens [B, S] -> (logits [B, S, V], argmax ids [B, S])."""
+def forced_logits_gpu(dec, wl, tokens, rows=None):
+    """Teacher-forced run through aed_decode_step: tokens [B, S] -> (logits [B, S, V], argmax ids [B, S]).
+    rows: keep only these sequences' logits and ids (a large batch's full logits do not fit the host)."""
     import torch
     B, S = tokens.shape
     dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
     tok_dev = torch.from_numpy(np.ascontiguousarray(tokens.T)).to(dec.device)  # [S, B]
+    sel = None if rows is None else torch.as_tensor(list(rows), dtype=torch.long, device=dec.device)
     logits, ids = [], []
     for s in range(S):
         out, lg = dec.aed_decode_step(tok_dev[s].contiguous())
-        logits.append(lg)
-        ids.append(out)
+        logits.append(lg if sel is None else lg[sel])
+        ids.append(out if sel is None else out[sel])
     torch.cuda.synchronize()
     return (torch.stack(logits, 1).cpu().numpy().astype(np.float64), torch.stack(ids, 1).cpu().numpy())
 

@@ -63,7 +63,8 @@ def test_canary24_b64_sampled_sequences(oracle):
 
 def _forced_check(oracle, wl, sample, n_new, tol, max_dec_len=None):
     """Greedy-decode the oracle on the sampled sequences for n_new tokens, then run the whole batch through
-    the HIP step path teacher-forced (sampled rows on the oracle's tokens, the rest on token 5) and compare."""
+    the HIP step path teacher-forced (sampled rows on the oracle's tokens, the rest on token 5) and compare
+    every logit of the sampled rows; then the sampled rows' cached self-attention keys and values."""
     import torch
     from tests import gpu_util as G
     cfg = wl.cfg
@@ -76,8 +77,18 @@ def _forced_check(oracle, wl, sample, n_new, tol, max_dec_len=None):
     for i, b in enumerate(sample):
         forced[b, P:] = ref_toks[i, :-1]
     dec = G.make_decoder(wl, max_dec_len=max_dec_len, poison=True)
-    glog, gids = G.forced_logits_gpu(dec, wl, forced)
-    err, near = G.check_forced(ref_logits, glog[sample][:, P - 1:], gids[sample][:, P - 1:], tol)
+    glog, gids = G.forced_logits_gpu(dec, wl, forced, rows=sample)
+    err, near = G.check_forced(ref_logits, glog[:, P - 1:], gids[:, P - 1:], tol)
+    # the paged cache after the run: every position of the sampled sequences, first and last layer (with 8-bit
+    # caches the contents are compared code by code in their own test)
+    for i, b in enumerate([] if getattr(cfg, "kv_fp8", 0) else sample[:2]):
+        one = wl.subset([b])
+        for layer in (0, cfg.n_layers - 1):
+            Kr, Vr = m.self_kv(layer, one.enc, forced[b])
+            Kg, Vg = dec.aed_read_self_kv(layer, b)
+            assert Kg.shape == Kr.shape
+            kerr = max(float(np.abs(Kg - Kr).max()), float(np.abs(Vg - Vr).max()))
+            assert kerr <= tol, f"self K/V of sequence {b}, layer {layer}: {kerr:.3e} > {tol}"
     return dec, err, near
 
 
@@ -87,7 +98,9 @@ def test_flash4_b256_sampled_sequences(oracle):
     import torch
     wl = W.make("flash4_b256")
     sample = [0, 100, 201, 255]
-    dec, err, near = _forced_check(oracle, wl, sample, 40, G.TOL["bf16"])
+    # all 128 new tokens: 132 cached positions = 9 pages per sequence, so that each of the attention kernel's four
+    # wavefronts goes round its block loop three times (pages looked up in the table, both register buffers refilled)
+    dec, err, near = _forced_check(oracle, wl, sample, wl.cfg.max_new, G.TOL["bf16"])
     print(f"flash4_b256 teacher-forced: max |dlogit| = {err:.3e}, near ties {near}")
     # the graph path at full length: every sequence emits exactly max_new tokens, run twice bit-identical
     dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
@@ -134,12 +147,45 @@ def test_ragged24_b128_forced_eos(oracle):
     dec.close()
 
 
-def test_large24_b1024_paged_sampled_sequences(oracle):
-    """Large batch: 1024 sequences of 500 frames, capacity for 452 positions in 16-token pages
-    (about 100 GB of workspace); a short teacher-forced run crossing one page boundary."""
+def test_large24_b1024_paged_sampled_sequences(oracle, capsys):
+    """Large batch: 1024 sequences of 500 frames, capacity for 452 positions in 16-token pages (about 100 GB of
+    workspace).  Teacher-forced on random tokens through all 451 positions (29 pages per sequence): the first and
+    the last sequence's logits against the oracle at every step, and the last layer's cached keys and values of
+    the first sequence.  The oracle's two passes run side by side (they are independent); a line is printed
+    after each phase because the whole test takes a few minutes."""
+    import threading
+    import time
     from tests import gpu_util as G
+
+    def say(msg):
+        with capsys.disabled():
+            print(f"\n[large24_b1024] {msg}", flush=True)
+
+    t0 = time.time()
     wl = W.make("large24_b1024")
+    cfg = wl.cfg
+    tol = G.TOL["bf16"]
     sample = [0, 1023]
-    dec, err, near = _forced_check(oracle, wl, sample, 16, G.TOL["bf16"], max_dec_len=wl.cfg.max_dec_len)
-    print(f"large24_b1024 teacher-forced: max |dlogit| = {err:.3e}, near ties {near}")
+    B, S = len(wl.enc_lens), cfg.prompt_len + cfg.max_new - 1
+    toks = np.random.default_rng(44).integers(3, cfg.vocab, size=(B, S)).astype(np.int32)
+    say(f"inputs drawn ({time.time() - t0:.0f} s); oracle: {len(sample)} sequences x {S} positions x {cfg.n_layers} layers")
+    sub = wl.subset(sample)
+    m = oracle.Model(cfg, wl.weights)
+    res = {}
+    first = wl.subset(sample[:1])
+    th = threading.Thread(target=lambda: res.update(kv=m.self_kv(cfg.n_layers - 1, first.enc, toks[sample[0]])))
+    th.start()
+    ref = m.decode_forced(sub.enc, sub.enc_lens, toks[sample])
+    say(f"oracle logits done ({time.time() - t0:.0f} s)")
+    dec = G.make_decoder(wl, max_dec_len=cfg.max_dec_len, poison=True)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks, rows=sample)
+    say(f"HIP path done ({time.time() - t0:.0f} s)")
+    err, near = G.check_forced(ref, glog, gids, tol)
+    th.join()
+    Kr, Vr = res["kv"]
+    Kg, Vg = dec.aed_read_self_kv(cfg.n_layers - 1, sample[0])
+    assert Kg.shape == Kr.shape == (S, cfg.d_model)
+    kerr = max(float(np.abs(Kg - Kr).max()), float(np.abs(Vg - Vr).max()))
+    assert kerr <= tol, f"self K/V of sequence {sample[0]}, last layer: {kerr:.3e} > {tol}"
+    say(f"teacher-forced over {S} positions: max |dlogit| = {err:.3e}, near ties {near}, max |dK,dV| = {kerr:.3e}")
     dec.close()

@@ -51,7 +51,9 @@ def test_tiny_fp32_teacher_forced_and_greedy(torch_cuda, oracle):
             Kg, Vg = dec.aed_read_cross_kv(layer, b, int(wl.enc_lens[b]))
             assert np.abs(Kg - Kr).max() < 1e-4 and np.abs(Vg - Vr).max() < 1e-4
             Ks, Vs = dec.aed_read_self_kv(layer, b)
-            assert Ks.shape[0] == full.shape[1] and np.isfinite(Ks).all() and np.isfinite(Vs).all()
+            Kr, Vr = m.self_kv(layer, sub.enc, full[b])
+            assert Ks.shape == Kr.shape
+            assert np.abs(Ks - Kr).max() < 1e-4 and np.abs(Vs - Vr).max() < 1e-4
     # free-running greedy through the captured graph
     torch = torch_cuda
     dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
@@ -100,10 +102,13 @@ def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head
     # determinism: a second run is bit-identical
     glog2, gids2 = G.forced_logits_gpu(dec, wl, toks)
     assert (glog2 == glog).all() and (gids2 == gids).all()
-    # cached self K/V equal the oracle's k, v for the fed tokens (checked via the padded routine's
-    # agreement elsewhere; here: finite and of the right length)
-    Ks, Vs = dec.aed_read_self_kv(1, 0)
-    assert Ks.shape == (S, d_model) and np.isfinite(Ks).all() and np.isfinite(Vs).all()
+    # the paged self-attention cache (S positions cross one or two page boundaries) against the oracle's keys and
+    # values of the fed tokens: a wrong page, slot or head offset in the append shows here
+    for b in (0, len(enc_lens) - 1):
+        Kr, Vr = m.self_kv(1, wl.subset([b]).enc, toks[b])
+        Ks, Vs = dec.aed_read_self_kv(1, b)
+        assert Ks.shape == (S, d_model) and np.isfinite(Ks).all() and np.isfinite(Vs).all()
+        assert np.abs(Ks - Kr).max() <= G.TOL[dtype] and np.abs(Vs - Vr).max() <= G.TOL[dtype]
     dec.close()
 
 
@@ -422,4 +427,96 @@ def test_same_shape_other_lengths_on_one_decoder(torch_cuda, oracle):
         glog, gids = G.forced_logits_gpu(dec, wl, forced)
         P = wl.cfg.prompt_len
         G.check_forced(ref_logits, glog[:, P - 1:], gids[:, P - 1:], G.TOL["bf16"])
+    dec.close()
+
+
+# ---------------------------------------------------------------- exact ties in the sampler
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("lo,hi", [
+    (8, 200),      # two lanes of the sampler's first wavefront
+    (8, 1032),     # one thread's first and second 4-vector
+    (600, 1030),   # the lower id sits in the third wavefront, the higher one in the first
+    (255, 256),    # neighbours across a wavefront boundary
+    (1023, 1024),  # last id of the last wavefront's first round, first id of the first wavefront's second round
+])
+def test_exact_ties_pick_the_lowest_id(torch_cuda, oracle, dtype, lo, hi):
+    """Two vocabulary rows with identical weights and bias give bit-equal logits; raised above all others they tie
+    for the maximum at every step.  The sampler must return the lower id (as the oracle's argmax does), wherever
+    the two ids sit in its reduction: in one thread, in one wavefront, in different wavefronts."""
+    from tests import gpu_util as G
+    torch = torch_cuda
+    wl = unit_workload(dtype, 256, 4, 64, [9, 30, 4], seed=31, vocab=2048, max_new=6)
+    w = wl.weights
+    w["w_out"][hi] = w["w_out"][lo]
+    w["b_out"][lo] = w["b_out"][hi] = 10.0   # random logits of this model stay below 2
+    m = oracle.Model(wl.cfg, w)
+    toks = random_tokens(wl.cfg, 3, 5, 32)
+    ref = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    assert (ref[..., lo] == ref[..., hi]).all() and (ref.argmax(-1) == lo).all()   # numpy's argmax: first maximum
+    for b in range(3):
+        for s in range(5):
+            assert oracle.argmax(ref[b, s]) == lo
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    assert (glog[..., lo] == glog[..., hi]).all(), "equal rows of the output matrix give unequal logits"
+    assert (glog.argmax(-1) == lo).all()
+    assert (gids == lo).all(), f"sampler picked {np.unique(gids).tolist()} on a tie of {lo} and {hi}"
+    # the greedy path's sampler (prompt feeding, output writes) on the same tie
+    dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+    out, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), 6)
+    assert (out.cpu().numpy() == lo).all() and (lens.cpu().numpy() == 6).all()
+    dec.close()
+
+
+# ---------------------------------------------------------------- bf16 logits while sequences finish
+def test_bf16_logits_through_finished_and_forced_eos(torch_cuda, oracle):
+    """Greedy decoding in bf16 mode with a natural EOS and per-sequence forced ends: the logits of every step,
+    read back after greedy runs of 1, 2, ... tokens (a run of n tokens ends with step n's logits in place), against
+    the oracle's greedy logits, for every sequence still running at that step and as long as its tokens have
+    followed the oracle's.  Finished sequences stay in the batch: their rows go through the products but append
+    nothing, attend to nothing and emit padding."""
+    from tests import gpu_util as G
+    torch = torch_cuda
+    tol = G.TOL["bf16"]
+    N = 20
+    lens_enc = [9, 30, 4, 17, 52, 130]
+    wl0 = unit_workload("bf16", 256, 4, 64, lens_enc, seed=23, max_new=N)
+    free, _ = oracle.Model(wl0.cfg, wl0.weights).greedy_decode(wl0.enc, wl0.enc_lens, wl0.prompt, N)
+    s_eos = next(s for s in range(4, N) if free[1, s] not in free[1, :s])
+    eos = int(free[1, s_eos])                  # sequence 1 emits this id for the first time at step s_eos >= 4
+    wl = unit_workload("bf16", 256, 4, 64, lens_enc, seed=23, max_new=N, eos_id=eos, pad_id=5)
+    m = oracle.Model(wl.cfg, wl.weights)
+    target = np.array([3, N, 1, 12, 30, 8], np.int32)
+    ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, N, max_new_per_seq=target,
+                                               want_logits=True)
+    assert ref_l[1] == s_eos + 1 and ref_l[2] == 1 and ref_l[0] <= 3
+    dec = G.make_decoder(wl)
+    prompt = torch.from_numpy(wl.prompt).to(dec.device)
+    B = len(lens_enc)
+    follows = np.ones(B, bool)     # the GPU's tokens have equalled the oracle's so far
+    worst, compared = 0.0, 0
+    for n in range(1, N + 1):
+        dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+        toks, lens = dec.aed_greedy_decode(prompt, n, max_new_per_seq=target)
+        toks, lens = toks.cpu().numpy(), lens.cpu().numpy()
+        lg = dec.aed_read_logits().astype(np.float64)
+        if (ref_l < n).all():
+            break                  # every sequence had finished before step n: the run stopped early
+        for b in range(B):
+            if ref_l[b] < n or not follows[b]:
+                continue           # finished before this step (row unspecified), or on another path
+            e = float(np.abs(lg[b] - ref_logits[b, n - 1]).max())
+            worst, compared = max(worst, e), compared + 1
+            assert e <= tol, f"step {n}, sequence {b}: |dlogit| {e:.3e}"
+            srt = np.sort(ref_logits[b, n - 1])
+            forced = n >= target[b]
+            if forced:
+                assert toks[b, n - 1] == eos
+            elif srt[-1] - srt[-2] > 2 * tol:
+                assert toks[b, n - 1] == ref_t[b, n - 1]
+            follows[b] = toks[b, n - 1] == ref_t[b, n - 1]
+            if ref_l[b] == n and follows[b]:
+                assert lens[b] == n
+    assert compared >= 30
+    print(f"bf16 greedy logits with finished rows in the batch: {compared} rows compared, max |dlogit| = {worst:.3e}")
     dec.close()
