@@ -141,6 +141,24 @@ aed_status aed_cross_kv_precompute_padded(aed_decoder *dec, const void *enc_padd
 aed_status aed_decode_step(aed_decoder *dec, const int32_t *tokens_in,
                            int32_t *tokens_out, float *logits_out);
 
+/* aed_decode_step for callers that cannot allocate device memory at this
+ * point or hand the library memory it may keep writing to behind their back:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same results, same errors.  The step's
+ * activations and attention partials live in a static device array of 8 MiB
+ * inside the library (each GPU the library runs on holds its copy until the
+ * process ends) instead of the workspace, the kernels are launched directly
+ * (no launch graph is built), the page table is advanced by a kernel instead
+ * of a host copy, and the call makes no allocation of any kind.
+ * Additional error: AED_ECAPACITY when the decoder's step activations do not
+ * fit the array (they grow with max_batch * (5 d_model + d_ffn + vocab);
+ * max_batch 64 of the 1024-wide configurations fits).
+ * Every decoder on a GPU shares that GPU's array, which keeps what the last
+ * call left in it: calls that overlap on one GPU (two streams, two threads)
+ * race.  Steps of this call and of aed_decode_step may be mixed. */
+aed_status aed_decode_step_noalloc(aed_decoder *dec, const int32_t *tokens_in,
+                                   int32_t *tokens_out, float *logits_out);
+
 /* Greedy decoding of the whole batch from a fixed-length prompt.  Restarts
  * the decode state of the current batch (cross K/V are kept), feeds the
  * prompt, then emits up to max_new tokens per sequence.

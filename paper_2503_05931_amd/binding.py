@@ -26,7 +26,7 @@ KERNEL_NAMES = ["ln_qkv", "self_attn", "self_out", "ln_crossq", "cross_attn", "c
                 "ln_vocab", "sample", "embed", "cross_kv"]
 
 EXPORTS = ("aed_workspace_bytes", "aed_decoder_create", "aed_decoder_destroy", "aed_cross_kv_precompute",
-           "aed_cross_kv_precompute_padded", "aed_decode_step", "aed_greedy_decode", "aed_greedy_decode_queue",
+           "aed_cross_kv_precompute_padded", "aed_decode_step", "aed_decode_step_noalloc", "aed_greedy_decode", "aed_greedy_decode_queue",
            "aed_last_error",
            "aed_layer_matrix_params", "aed_read_cross_kv", "aed_read_self_kv", "aed_read_logits", "aed_time_kernels",
            "aed_kernel_work")
@@ -73,6 +73,7 @@ def load():
     lib.aed_cross_kv_precompute.argtypes = [vp, vp, i32p, C.c_int32]
     lib.aed_cross_kv_precompute_padded.argtypes = [vp, vp, C.c_int32, i32p, C.c_int32]
     lib.aed_decode_step.argtypes = [vp, vp, vp, vp]
+    lib.aed_decode_step_noalloc.argtypes = [vp, vp, vp, vp]
     lib.aed_greedy_decode.argtypes = [vp, vp, C.c_int32, C.c_int32, i32p, vp, vp]
     lib.aed_greedy_decode_queue.argtypes = [vp, vp, i32p, C.c_int32, vp, C.c_int32, C.c_int32, i32p, vp, vp, i32p]
     lib.aed_last_error.argtypes = [vp]
@@ -228,6 +229,13 @@ class Decoder:
                                              C.c_void_p(logits.data_ptr()) if want_logits else None))
         self._exit()
         return out, logits
+
+    def aed_decode_step_noalloc(self, tokens_in, tokens_out, logits_out=None):
+        """The step with caller-provided output tensors (device int32 [batch], float32 [batch, vocab] or None);
+        nothing is allocated on the way."""
+        self._check(self.lib.aed_decode_step_noalloc(
+            self.handle, C.c_void_p(tokens_in.data_ptr()), C.c_void_p(tokens_out.data_ptr()),
+            C.c_void_p(logits_out.data_ptr()) if logits_out is not None else None))
 
     def aed_greedy_decode(self, prompt, max_new: int, max_new_per_seq=None, out_tokens=None, out_lens=None):
         """prompt: device int32 [batch, P].  Returns (tokens [batch, max_new], lens [batch]), device tensors."""

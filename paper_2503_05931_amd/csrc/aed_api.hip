@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -17,7 +18,35 @@
 
 using namespace aed;
 
+// Scratch memory of aed_decode_step_noalloc: the step's activations and attention partials, for callers that
+// cannot hand over a workspace allocation of their own choosing at that point (see aed.h).  Every GPU the library
+// runs on holds its own copy until the process ends.  In host code this name is only a handle: the array's device
+// address comes from hipGetSymbolAddress, once per device (scratch_of_current_device).
+constexpr size_t kStaticScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// The static scratch array's address on the current device; resolved on first use per device.
+hipError_t scratch_of_current_device(char** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static char* ptr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = static_cast<char*>(p);
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
 
 constexpr int kMaxChunks = 8;       // split-K chunks per (sequence, head)
 constexpr int kTargetItems = 512;      // work items aimed at per attention launch when sequences are cut
@@ -32,6 +61,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
     size_t x, q, logits, attn_out, ffn_h, ln_h, x_shadow, ln_stats, mu_hat, ln_fold;
     size_t stats_elems;  // float2 per statistics buffer
+    size_t act_bytes;    // [0, act_bytes): the step's activations and attention partials (x ... counters)
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished, step_tok;
     size_t prompt_buf, out_buf, page_table, enc_off, row_map, frame_map, turn_buf, items, part, counters;
     size_t v_seq_len, v_finished, v_cur_tok, v_page_table, v_items;  // state of a prompt-prefill pass's rows
@@ -96,6 +126,9 @@ void make_layout(const aed_config* c, Layout* L) {
     L->stats_elems = (d / 16) * Bp;
     L->ln_stats = take(2 * L->stats_elems * 8);
     L->mu_hat = take(2 * Bp * 4);  // two buffers, alternating like the statistics
+    L->part = take(Ba * H * kMaxChunks * (Dh + 2) * 4);
+    L->counters = take(Ba * H * 4);
+    L->act_bytes = off;  // everything above is rewritten by every step before it is read (the counters: zero between launches)
     L->ln_fold = take(((size_t)c->n_layers * (4 * d + (size_t)c->d_ffn) + (size_t)c->vocab) * 2 * 4);
     L->seq_len = take(B * 4);
     L->n_gen = take(B * 4);
@@ -113,8 +146,6 @@ void make_layout(const aed_config* c, Layout* L) {
     L->frame_map = take((size_t)c->max_total_enc_frames * 4);  // request queue: where each new frame's K/V goes
     L->turn_buf = take(B * 4 * 4);                            // request queue: slot, old / new request, limit
     L->items = take((size_t)L->max_items * 16);
-    L->part = take(Ba * H * kMaxChunks * (Dh + 2) * 4);
-    L->counters = take(Ba * H * 4);
     L->v_seq_len = take(Ba * 4);
     L->v_finished = take(Ba * 4);
     L->v_cur_tok = take(Ba * 4);
@@ -170,6 +201,8 @@ struct aed_decoder {
     const void* fw_out = nullptr;
     hipStream_t stream;
     char* ws;
+    char* act;             // where the step's activations live: ws, or this device's static scratch array
+    char* static_scratch = nullptr;  // this device's copy of the static scratch array
     // host-side state
     enum State { NO_BATCH, STEPPING, CONSUMED } state = NO_BATCH;
     int batch = 0;
@@ -195,6 +228,7 @@ struct aed_decoder {
     std::string err;
 
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+    template <typename T> T* act_at(size_t off) const { return reinterpret_cast<T*>(act + off); }
     StateArgs state_args(int prompt_len, int max_new) const {
         StateArgs st;
         st.seq_len = at<int>(lay.seq_len);
@@ -259,7 +293,7 @@ GemmArgs gemm_base(const aed_decoder* d, int layer) {
     GemmArgs g;
     memset(&g, 0, sizeof g);
     g.ln_eps = d->cfg.ln_eps;
-    g.ln_scratch = d->ws + d->lay.ln_h;
+    g.ln_scratch = d->act + d->lay.ln_h;
     g.M = d->batch;
     g.n_heads = d->cfg.n_heads;
     g.head_dim = d->cfg.head_dim;
@@ -272,13 +306,13 @@ GemmArgs gemm_base(const aed_decoder* d, int layer) {
 // bfloat16 mode: the LayerNorm products read the shadow of the residual rows and their statistics
 bool folded_ln(const aed_decoder* d) { return d->dt == kBF16; }
 float2* stats_buf(const aed_decoder* d, int par) {
-    return reinterpret_cast<float2*>(d->ws + d->lay.ln_stats) + (size_t)par * d->lay.stats_elems;
+    return reinterpret_cast<float2*>(d->act + d->lay.ln_stats) + (size_t)par * d->lay.stats_elems;
 }
 float* shift_buf(const aed_decoder* d, int par) {
-    return d->at<float>(d->lay.mu_hat) + (size_t)par * (d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+    return d->act_at<float>(d->lay.mu_hat) + (size_t)par * (d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
 }
 void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float* c2) {
-    g.A = d->ws + d->lay.x_shadow;
+    g.A = d->act + d->lay.x_shadow;
     // rows of version v (parity p): statistics in buffer p; the shadow was shifted by the mean of version v-1,
     // which that version's product left in shift buffer p^1; this product leaves the mean of version v in buffer p
     g.stats_in = stats_buf(d, d->x_par);
@@ -293,10 +327,10 @@ void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float
 hipError_t k_ln_qkv(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d, l);
-    g.A = d->at<float>(d->lay.x);
+    g.A = d->act_at<float>(d->lay.x);
     g.W = d->fw[l].w_qkv; g.bias = w.b_qkv; g.ln_g = w.ln1_g; g.ln_b = w.ln1_b;
     g.N = 3 * d->cfg.d_model; g.K = d->cfg.d_model;
-    g.out = d->at<float>(d->lay.q);
+    g.out = d->act_at<float>(d->lay.q);
     g.k_pool = d->ws + d->lay.k_pool + (size_t)l * d->lay.pool_layer_elems * d->kv_esz;
     g.v_pool = d->ws + d->lay.v_pool + (size_t)l * d->lay.pool_layer_elems * d->kv_esz;
     g.page_table = d->at<int>(d->lay.page_table);
@@ -313,11 +347,11 @@ hipError_t k_ln_qkv(aed_decoder* d, int l) {
 AttnArgs attn_base(const aed_decoder* d) {
     AttnArgs a;
     memset(&a, 0, sizeof a);
-    a.q = d->at<float>(d->lay.q);
-    a.out = d->ws + d->lay.attn_out;
+    a.q = d->act_at<float>(d->lay.q);
+    a.out = d->act + d->lay.attn_out;
     a.finished = d->at<int>(d->lay.finished);
-    a.part = d->at<float>(d->lay.part);
-    a.counters = d->at<int>(d->lay.counters);
+    a.part = d->act_at<float>(d->lay.part);
+    a.counters = d->act_at<int>(d->lay.counters);
     a.max_chunks = kMaxChunks;
     a.n_heads = d->cfg.n_heads;
     a.head_dim = d->cfg.head_dim;
@@ -344,11 +378,11 @@ hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const vo
     GemmArgs g = gemm_base(d, l);
     g.A = A; g.W = W; g.bias = bias;
     g.N = d->cfg.d_model; g.K = K;
-    g.out = d->at<float>(d->lay.x);
+    g.out = d->act_at<float>(d->lay.x);
     if (folded_ln(d)) {
         g.stats_out = stats_buf(d, d->x_par ^ 1);
         g.mu_hat_in = shift_buf(d, d->x_par);  // mean of the rows before the update, left by the product that read them
-        g.shadow_out = d->ws + d->lay.x_shadow;
+        g.shadow_out = d->act + d->lay.x_shadow;
         g.shadow_g = next_g;
         g.stat_tiles = d->cfg.d_model / 16;
         g.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
@@ -361,10 +395,10 @@ hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const vo
 hipError_t k_ln_crossq(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d, l);
-    g.A = d->at<float>(d->lay.x);
+    g.A = d->act_at<float>(d->lay.x);
     g.W = d->fw[l].w_cq; g.bias = w.b_cq; g.ln_g = w.ln2_g; g.ln_b = w.ln2_b;
     g.N = d->cfg.d_model; g.K = d->cfg.d_model;
-    g.out = d->at<float>(d->lay.q);
+    g.out = d->act_at<float>(d->lay.q);
     if (folded_ln(d)) {
         ln_consumer(d, g, d->fold[l].cq_c1, d->fold[l].cq_c2);
         return launch_gemm(d->dt, PRO_LNS, EPI_F32, g, d->stream);
@@ -387,10 +421,10 @@ hipError_t k_cross_attn(aed_decoder* d, int l) {
 hipError_t k_ln_ffn1(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
     GemmArgs g = gemm_base(d, l);
-    g.A = d->at<float>(d->lay.x);
+    g.A = d->act_at<float>(d->lay.x);
     g.W = d->fw[l].w_ff1; g.bias = w.b_ff1; g.ln_g = w.ln3_g; g.ln_b = w.ln3_b;
     g.N = d->cfg.d_ffn; g.K = d->cfg.d_model;
-    g.out = d->ws + d->lay.ffn_h;
+    g.out = d->act + d->lay.ffn_h;
     if (folded_ln(d)) {
         ln_consumer(d, g, d->fold[l].ff1_c1, d->fold[l].ff1_c2);
         return launch_gemm(d->dt, PRO_LNS, EPI_RELU_T, g, d->stream);
@@ -400,10 +434,10 @@ hipError_t k_ln_ffn1(aed_decoder* d, int l) {
 
 hipError_t k_ln_vocab(aed_decoder* d) {
     GemmArgs g = gemm_base(d, d->cfg.n_layers);
-    g.A = d->at<float>(d->lay.x);
+    g.A = d->act_at<float>(d->lay.x);
     g.W = d->fw_out; g.bias = d->w.b_out; g.ln_g = d->w.lnf_g; g.ln_b = d->w.lnf_b;
     g.N = d->cfg.vocab; g.K = d->cfg.d_model;
-    g.out = d->at<float>(d->lay.logits);
+    g.out = d->act_at<float>(d->lay.logits);
     if (folded_ln(d)) {
         ln_consumer(d, g, d->out_c1, d->out_c2);
         return launch_gemm(d->dt, PRO_LNS, EPI_F32, g, d->stream);
@@ -432,13 +466,13 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
     switch (cls) {
         case AED_K_LN_QKV: return k_ln_qkv(d, l);
         case AED_K_SELF_ATTN: return k_self_attn(d, l);
-        case AED_K_SELF_OUT: return k_resid(d, l, d->ws + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model, w.ln2_g);
+        case AED_K_SELF_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model, w.ln2_g);
         case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
         case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
-        case AED_K_CROSS_OUT: return k_resid(d, l, d->ws + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model, w.ln3_g);
+        case AED_K_CROSS_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model, w.ln3_g);
         case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
         case AED_K_FFN2:
-            return k_resid(d, l, d->ws + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn,
+            return k_resid(d, l, d->act + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn,
                            l + 1 < d->cfg.n_layers ? d->layers[l + 1].ln1_g : d->w.lnf_g);
         case AED_K_CROSS_KV: return k_cross_kv(d, l, d->total_enc, nullptr);
         default: return hipErrorInvalidValue;
@@ -452,20 +486,20 @@ hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* st
     memset(&sa, 0, sizeof sa);
     if (folded_ln(d)) {
         d->x_par = 0;
-        sa.shadow = d->ws + d->lay.x_shadow;
+        sa.shadow = d->act + d->lay.x_shadow;
         sa.g = d->layers[0].ln1_g;
         sa.stats = stats_buf(d, 0);
         sa.mu_hat = shift_buf(d, 1);  // read as the shift of version 0 by the first product
         sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
     }
-    e = launch_embed(d->dt, d->at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
+    e = launch_embed(d->dt, d->act_at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
                      d->cfg.max_positions, d->cfg.emb_scale, sa, d->stream);
     if (e != hipSuccess) return e;
     for (int l = 0; l < d->cfg.n_layers; ++l)
         for (int cls = AED_K_LN_QKV; cls <= AED_K_FFN2; ++cls)
             if ((e = k_class(d, cls, l)) != hipSuccess) return e;
     if ((e = k_ln_vocab(d)) != hipSuccess) return e;
-    return launch_sample(d->at<float>(d->lay.logits), st, greedy, step_out, d->stream);
+    return launch_sample(d->act_at<float>(d->lay.logits), st, greedy, step_out, d->stream);
 }
 
 aed_status check_weights(const aed_config* c, const aed_weights* w) {
@@ -635,13 +669,13 @@ aed_status prefill_pass(aed_decoder* d, const std::vector<int>& prompt_host, int
         memset(&sa, 0, sizeof sa);
         if (folded_ln(d)) {
             d->x_par = 0;
-            sa.shadow = d->ws + d->lay.x_shadow;
+            sa.shadow = d->act + d->lay.x_shadow;
             sa.g = d->layers[0].ln1_g;
             sa.stats = stats_buf(d, 0);
             sa.mu_hat = shift_buf(d, 1);
             sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
         }
-        hipError_t e = launch_embed(d->dt, d->at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
+        hipError_t e = launch_embed(d->dt, d->act_at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
                                     d->cfg.max_positions, d->cfg.emb_scale, sa, d->stream);
         for (int l = 0; l < d->cfg.n_layers && e == hipSuccess; ++l) {
             const int last_cls = l + 1 < d->cfg.n_layers ? AED_K_FFN2 : AED_K_LN_QKV;
@@ -720,12 +754,14 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
     d->w.layers = d->layers.data();
     d->stream = static_cast<hipStream_t>(hip_stream);
     d->ws = static_cast<char*>(workspace);
+    d->act = d->ws;
     auto cleanup = [&](hipError_t e, const char* what) {
         fail(nullptr, AED_EHIP, "%s: %s", what, hipGetErrorString(e));
         aed_decoder_destroy(d);
         return AED_EHIP;
     };
     hipError_t e;
+    if ((e = scratch_of_current_device(&d->static_scratch)) != hipSuccess) return cleanup(e, "hipGetSymbolAddress(scratch)");
     // two poll words, then (from word 64) one finished flag per sequence for the request queue
     if ((e = hipHostMalloc(reinterpret_cast<void**>(&d->pin_poll), 256 + (size_t)cfg->max_batch * 4,
                            hipHostMallocDefault)) != hipSuccess)
@@ -825,6 +861,7 @@ aed_status aed_decode_step(aed_decoder* d, const int32_t* tokens_in, int32_t* to
     if (d->host_pos >= d->cfg.max_dec_len || d->host_pos >= d->cfg.max_positions)
         return fail(d, AED_ECAPACITY, "position %d exceeds max_dec_len %d / max_positions %d", d->host_pos,
                     d->cfg.max_dec_len, d->cfg.max_positions);
+    d->act = d->ws;
     if (d->host_pos % kPage == 0) {  // every sequence enters a new page
         if (d->pages_used + d->batch > d->lay.n_pages)
             return fail(d, AED_ECAPACITY, "self-attention page pool exhausted (%d pages)", d->lay.n_pages);
@@ -851,7 +888,42 @@ aed_status aed_decode_step(aed_decoder* d, const int32_t* tokens_in, int32_t* to
         HIP_TRY(d, enqueue_step(d, st, 0, tokens_out));
     }
     if (logits_out)
-        HIP_TRY(d, hipMemcpyAsync(logits_out, d->at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4,
+        HIP_TRY(d, hipMemcpyAsync(logits_out, d->act_at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4,
+                                  hipMemcpyDeviceToDevice, d->stream));
+    d->host_pos += 1;
+    return AED_OK;
+}
+
+aed_status aed_decode_step_noalloc(aed_decoder* d, const int32_t* tokens_in, int32_t* tokens_out, float* logits_out) {
+    if (!d) return AED_EINVAL;
+    if (d->state != aed_decoder::STEPPING)
+        return fail(d, AED_ESTATE, "aed_decode_step_noalloc needs a batch started by aed_cross_kv_precompute");
+    if (!tokens_in) return fail(d, AED_EINVAL, "tokens_in is NULL");
+    if (d->lay.act_bytes > kStaticScratchBytes)
+        return fail(d, AED_ECAPACITY,
+                    "this decoder's step activations take %zu bytes (max_batch %d, d_model %d, d_ffn %d, vocab %d); "
+                    "the static scratch array holds %zu",
+                    d->lay.act_bytes, d->cfg.max_batch, d->cfg.d_model, d->cfg.d_ffn, d->cfg.vocab, kStaticScratchBytes);
+    if (d->host_pos >= d->cfg.max_dec_len || d->host_pos >= d->cfg.max_positions)
+        return fail(d, AED_ECAPACITY, "position %d exceeds max_dec_len %d / max_positions %d", d->host_pos,
+                    d->cfg.max_dec_len, d->cfg.max_positions);
+    if (d->host_pos % kPage == 0) {  // every sequence enters a new page: the table entries are written by a kernel
+        if (d->pages_used + d->batch > d->lay.n_pages)
+            return fail(d, AED_ECAPACITY, "self-attention page pool exhausted (%d pages)", d->lay.n_pages);
+        const int blk = d->host_pos / kPage;
+        HIP_TRY(d, launch_assign_pages(d->at<int>(d->lay.page_table), d->lay.max_pages, blk, d->pages_used, d->batch,
+                                       d->stream));
+        for (int b = 0; b < d->batch; ++b) d->page_table[(size_t)b * d->lay.max_pages + blk] = d->pages_used++;
+    }
+    d->act = d->static_scratch;
+    // the array keeps what the last call on this GPU left: the merge's arrival counters must start at zero, all
+    // other buffers are written by this step before they are read
+    HIP_TRY(d, launch_fill_zero(d->act_at<int>(d->lay.counters), d->lay.act_rows * d->cfg.n_heads, d->stream));
+    StateArgs st = d->state_args(0, 0);
+    HIP_TRY(d, launch_set_tokens(st.cur_tok, tokens_in, 1, d->batch, d->stream));
+    HIP_TRY(d, enqueue_step(d, st, 0, tokens_out));
+    if (logits_out)
+        HIP_TRY(d, hipMemcpyAsync(logits_out, d->act_at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4,
                                   hipMemcpyDeviceToDevice, d->stream));
     d->host_pos += 1;
     return AED_OK;
@@ -864,6 +936,7 @@ aed_status aed_greedy_decode(aed_decoder* d, const int32_t* prompt, int32_t prom
         return fail(d, AED_ESTATE, "aed_greedy_decode needs a batch started by aed_cross_kv_precompute");
     if (!prompt || !out_tokens || !out_lens) return fail(d, AED_EINVAL, "prompt / out_tokens / out_lens is NULL");
     if (prompt_len < 1 || max_new < 1) return fail(d, AED_EINVAL, "prompt_len and max_new must be >= 1");
+    d->act = d->ws;
     if (max_new_per_seq) {
         if (d->cfg.eos_id < 0) return fail(d, AED_EINVAL, "max_new_per_seq needs eos_id >= 0");
         for (int b = 0; b < d->batch; ++b)
@@ -980,6 +1053,7 @@ extern "C" aed_status aed_greedy_decode_queue(aed_decoder* d, const void* enc_st
     if (n_requests < 1) return fail(d, AED_EINVAL, "n_requests must be >= 1");
     if (prompt_len < 1 || max_new < 1) return fail(d, AED_EINVAL, "prompt_len and max_new must be >= 1");
     if (d->cfg.eos_id < 0) return fail(d, AED_EINVAL, "the request queue needs eos_id >= 0");
+    d->act = d->ws;
     const int total_len = prompt_len + max_new;
     if (total_len > d->cfg.max_dec_len || total_len > d->cfg.max_positions)
         return fail(d, AED_ECAPACITY, "prompt_len + max_new = %d exceeds max_dec_len %d / max_positions %d", total_len,
@@ -1227,7 +1301,7 @@ aed_status aed_read_logits(aed_decoder* d, float* logits_out) {
     if (d->state == aed_decoder::NO_BATCH) return fail(d, AED_ESTATE, "no batch");
     if (!logits_out) return fail(d, AED_EINVAL, "logits_out is NULL");
     HIP_TRY(d, hipStreamSynchronize(d->stream));
-    HIP_TRY(d, hipMemcpy(logits_out, d->at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(d, hipMemcpy(logits_out, d->act_at<float>(d->lay.logits), (size_t)d->batch * d->cfg.vocab * 4, hipMemcpyDeviceToHost));
     return AED_OK;
 }
 
@@ -1237,6 +1311,7 @@ aed_status aed_time_kernels(aed_decoder* d, int32_t cls, int32_t reps, float* ms
     if (!ms_total || !launches || reps < 1) return fail(d, AED_EINVAL, "bad arguments");
     const bool per_layer = cls >= AED_K_LN_QKV && cls <= AED_K_FFN2;
     if (!per_layer && cls != AED_K_LN_VOCAB && cls != AED_K_CROSS_KV) return fail(d, AED_EINVAL, "kernel class cannot be timed alone");
+    d->act = d->ws;
     const int cap = d->state == aed_decoder::CONSUMED ? d->last_prompt_len + d->last_max_new : d->host_pos;
     StateArgs st = d->state_args(0, 0);
     HIP_TRY(d, launch_prepare_timing(st, std::max(0, std::min(cap, d->cfg.max_dec_len) - 1), d->stream));

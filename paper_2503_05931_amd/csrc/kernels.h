@@ -151,6 +151,11 @@ hipError_t launch_turn_over_slots(const StateArgs& st, const int* slots, const i
                                   const int* limits, int n, const int* all_prompts, int* dst_tokens, int* dst_lens,
                                   hipStream_t s);
 
+// page_table[b * max_pages + blk] = first_page + b for b < batch (the step API hands every sequence a new page at once)
+hipError_t launch_assign_pages(int* page_table, int max_pages, int blk, int first_page, int batch, hipStream_t s);
+// p[0 .. n) = 0
+hipError_t launch_fill_zero(int* p, int n, hipStream_t s);
+
 // finished[b] = 0, seq_len[b] = clamp(seq_len[b], 0, max_pos): a valid mid-decode state for timing runs
 hipError_t launch_prepare_timing(const StateArgs& st, int max_pos, hipStream_t s);
 

@@ -227,6 +227,29 @@ hipError_t launch_turn_over_slots(const StateArgs& st, const int* slots, const i
     return hipGetLastError();
 }
 
+__global__ void assign_pages_kernel(int* __restrict__ page_table, int max_pages, int blk, int first_page, int batch) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) page_table[(size_t)b * max_pages + blk] = first_page + b;
+}
+
+hipError_t launch_assign_pages(int* page_table, int max_pages, int blk, int first_page, int batch, hipStream_t s) {
+    if (batch < 1 || blk < 0 || blk >= max_pages) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(assign_pages_kernel, dim3((batch + 255) / 256), dim3(256), 0, s, page_table, max_pages, blk,
+                       first_page, batch);
+    return hipGetLastError();
+}
+
+__global__ void fill_zero_kernel(int* __restrict__ p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_fill_zero(int* p, int n, hipStream_t s) {
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
 __global__ void prepare_timing_kernel(StateArgs st, int max_pos) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= st.batch) return;
