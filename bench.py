@@ -121,6 +121,17 @@ def run_workload(name, steps, warmup, want_roofline, eager=False, no_prefill=Fal
         dom = max(per, key=lambda k: per[k]["us"])
         p = per[dom]
         res["kernels"] = {k: {"us": round(v["us"], 2), "GBps": round(v["GBps"], 1)} for k, v in per.items()}
+        # the projection products as MFMA work (flops / time against the dense bf16 peak); meaningful from batch 256 on,
+        # below that they are weight streams
+        res["mfma_projection"] = {
+            "M": B, "bound": "mfma", "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "kernels": {k: {"us": round(per[k]["us"], 2), "achieved": round(per[k]["TFLOPs"], 1),
+                            "frac": round(per[k]["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)}
+                        for k in ("ln_qkv", "ln_ffn1", "ffn2")}}
+        att = {k: per[k] for k in ("self_attn", "cross_attn")}
+        res["attention_hbm"] = {k: {"us": round(v["us"], 2), "achieved": round(v["GBps"], 1),
+                                    "frac": round(v["GBps"] / HBM_PEAK_GBS, 4), "bytes_per_launch": v["bytes"]}
+                                for k, v in att.items()}
         res["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": p["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": p["GBps"] / HBM_PEAK_GBS, "traffic": None if kv_fp8 else measured_traffic(dom, name),
                            "avg_launch_us": p["us"], "algorithmic_bytes_per_launch": p["bytes"]}
@@ -175,7 +186,10 @@ def run_ragged(steps, warmup):
     former = batching.Bucketing(pe, pd, 8, 2)
     batch_of, bucket_of_batch = former.aed_bucketing_form_batches(pe, pd, batching.FLEXIBLE, np.full(16, B, np.int32))
     bucketed = [np.where(batch_of == t)[0] for t in range(len(bucket_of_batch))]
-    bucketed = [x for x in bucketed if len(x) == B]
+    n_formed = len(bucketed)
+    bucketed = [x for x in bucketed if len(x) == B]   # timed: full batches only (the partial ones are counted below)
+    dropped = {"partial_batches": n_formed - len(bucketed),
+               "samples": int(len(pe) - sum(len(x) for x in bucketed))}
     cases = {"ragged_random": (W.random_batches(pe, pd, perm, B), False),
              "bucketed_2d": (bucketed, False),
              "padded_random": (W.random_batches(pe, pd, perm, B), True)}
@@ -188,6 +202,7 @@ def run_ragged(steps, warmup):
         out[name] = {"tokens_per_s": tokens / dt, "batches": len(batches), "tokens": tokens, "seconds": dt,
                      "padding_enc": W.padding_fraction([pe[i] for i in batches]),
                      "padding_dec": W.padding_fraction([pd[i] for i in batches])}
+    out["bucketed_2d"]["not_timed"] = dropped
     # case (d): the same samples as (a), in the same order, as one queue through B slots that are refilled as
     # sequences end.  The queue call takes every request's encoder states at once (values do not matter for timing).
     batches = cases["ragged_random"][0]
@@ -234,7 +249,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="canary24_b64")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-also", action="store_true", help="skip the 4-layer decoder's extra line")
+    ap.add_argument("--no-also", action="store_true", help="skip the extra workloads (4-layer decoder, large batch)")
+    ap.add_argument("--no-large", action="store_true", help="skip the large-batch workload of the extra lines")
     ap.add_argument("--no-prefill", action="store_true",
                     help="feed the prompt one position per decoder step instead of prefilling it in one pass")
     ap.add_argument("--kv-fp8", action="store_true",
@@ -291,8 +307,7 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {"workload": args.workload, "kv_cache": "fp8_e4m3" if args.kv_fp8 else cfg.dtype,
-                   "n_layers": cfg.n_layers, "d_model": cfg.d_model,
-                   "batch": cfg.batch, "prompt_len": cfg.prompt_len, "max_new": cfg.max_new,
+                   "prompt_len": cfg.prompt_len, "max_new": cfg.max_new,
                    "enc_frames_total": int(wl.enc_lens.sum()),
                    "step": "cross K/V precompute + greedy decode of the batch",
                    "launch": "eager" if args.eager else "graph",
@@ -304,14 +319,24 @@ def main():
         "kernels": res.get("kernels"),
         "roofline": res.get("roofline"),
         "mfma_roofline": res.get("mfma"),
+        "kernel_timing": "per kernel class: the class's launches of all layers replayed back to back between HIP events "
+                         "on the decoder's stream, mid-decode state",
     }
     if not args.no_also and args.workload == "canary24_b64":
-        r4, _ = run_workload("flash4_b256", args.steps, args.warmup, want_roofline=False, no_prefill=args.no_prefill,
-                             kv_fp8=args.kv_fp8)
-        line["also"] = [{"workload": "flash4_b256", "n_layers": 4, "batch": 256, "value": r4["tokens_per_s"],
-                         "unit": "tokens/s", "ms_per_step": r4["ms_per_step"],
-                         "decode_only_tokens_per_s": r4["decode_only_tokens_per_s"],
-                         "decoder_rtfx": r4.get("decoder_rtfx")}]
+        # the 4-layer decoder at batch 256 and the large batch (1024 x 500 frames, 448 steps): their own tokens/s, the
+        # attention kernels against the HBM roofline, the projection products against the MFMA roofline
+        line["also"] = []
+        for name, k, w in (("flash4_b256", args.steps, args.warmup), ("large24_b1024", min(args.steps, 2), min(args.warmup, 1))):
+            if name == "large24_b1024" and args.no_large:
+                continue
+            r, _ = run_workload(name, k, w, want_roofline=True, no_prefill=args.no_prefill, kv_fp8=args.kv_fp8)
+            line["also"].append({"workload": name, "value": r["tokens_per_s"], "unit": "tokens/s", "steps": k,
+                                 "warmup": w, "ms_per_step": r["ms_per_step"],
+                                 "decode_only_tokens_per_s": r["decode_only_tokens_per_s"],
+                                 "decode_ms_per_token_step": r["decode_ms_per_token_step"],
+                                 "decoder_rtfx": r.get("decoder_rtfx"), "roofline": r.get("roofline"),
+                                 "attention_hbm": r.get("attention_hbm"), "mfma_projection": r.get("mfma_projection"),
+                                 "mfma_roofline": r.get("mfma")})
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(line))
