@@ -19,6 +19,7 @@
  *
  * Conventions
  *  - All weight matrices are row-major [out, in]; a NULL bias pointer = zero.
+ *    norm_type 1 replaces every LayerNorm below by RMSNorm (aed_config).
  *  - dtype 0: weights / encoder states / KV caches are float32.
  *    dtype 1: they are bfloat16; the residual stream, LayerNorm statistics,
  *    scores, softmax, accumulators and logits are float32 in both modes.
@@ -60,7 +61,9 @@ typedef struct aed_config {
     uint32_t struct_size;  /* = sizeof(aed_config) */
     int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab, max_positions;
     int32_t dtype;         /* 0 float32, 1 bfloat16 */
-    int32_t norm_type;     /* 0 LayerNorm; others: AED_EUNSUPPORTED */
+    int32_t norm_type;     /* 0 LayerNorm: g (z - mean) / sqrt(biased variance + ln_eps) + b.
+                              1 RMSNorm in its place everywhere (ln1, ln2, ln3, lnf): g z / sqrt(mean(z^2) + ln_eps) + b,
+                              no mean subtraction; the shift vectors ln*_b may then be NULL (= zero) */
     int32_t page_size;     /* tokens per self-attention KV page (16) */
     int32_t max_batch;             /* capacity: sequences per batch */
     int32_t max_total_enc_frames;  /* capacity: sum of encoder lengths of a batch */
@@ -97,8 +100,7 @@ typedef struct aed_weights {
  * Errors: AED_EINVAL (NULL, struct_size mismatch, non-positive or inconsistent
  * dimensions, n_heads*head_dim != d_model), AED_EUNSUPPORTED (shape without a
  * kernel: head_dim not 64/128, d_model not a multiple of 256 or above 1024,
- * d_ffn not a multiple of 256, vocab not a multiple of 64, page_size != 16,
- * norm_type != 0). */
+ * d_ffn not a multiple of 256, vocab not a multiple of 64, page_size != 16). */
 aed_status aed_workspace_bytes(const aed_config *cfg, size_t *bytes);
 
 /* Create a decoder.  workspace: DEVICE memory, 256-byte aligned, at least

@@ -39,6 +39,23 @@ void aedo_layernorm(const double *z, const float *g, const float *b, int n, doub
     for (int i = 0; i < n; ++i) y[i] = (double)g[i] * ((z[i] - mean) * rstd) + (double)b[i];
 }
 
+void aedo_rmsnorm(const double *z, const float *g, const float *b, int n, double eps, double *y)
+{
+    double ms = 0.0;
+    for (int i = 0; i < n; ++i) ms += z[i] * z[i];
+    ms /= n;
+    double r = 1.0 / sqrt(ms + eps);
+    for (int i = 0; i < n; ++i) y[i] = (double)g[i] * (z[i] * r) + (b ? (double)b[i] : 0.0);
+}
+
+/* the normalisation the configuration names */
+static void norm_rows(const aedo_config *cfg, const double *z, const float *g, const float *b, int n, double eps,
+                      double *y)
+{
+    if (cfg->norm_type == 1) aedo_rmsnorm(z, g, b, n, eps, y);
+    else aedo_layernorm(z, g, b, n, eps, y);
+}
+
 void aedo_linear(const double *x, const float *W, const float *bias, int n_in, int n_out, double *y)
 {
     for (int o = 0; o < n_out; ++o) {
@@ -253,7 +270,7 @@ static void seq_step(const aedo_config *cfg, const aedo_weights *w, seq_state *s
     for (int l = 0; l < cfg->n_layers; ++l) {
         const aedo_layer *lw = &w->layers[l];
         /* causal self-attention: the cache holds positions 0..pos */
-        aedo_layernorm(s->x, lw->ln1_g, lw->ln1_b, d, eps, s->h);
+        norm_rows(cfg, s->x, lw->ln1_g, lw->ln1_b, d, eps, s->h);
         aedo_linear(s->h, lw->w_qkv, lw->b_qkv, d, 3 * d, s->qkv);
         if (cfg->kv_fp8) store_as_fp8(s->qkv + d, 2 * d);
         memcpy(s->Ks[l] + (size_t)pos * d, s->qkv + d, sizeof(double) * (size_t)d);
@@ -264,7 +281,7 @@ static void seq_step(const aedo_config *cfg, const aedo_weights *w, seq_state *s
         aedo_linear(s->att, lw->w_o, lw->b_o, d, d, s->proj);
         for (int i = 0; i < d; ++i) s->x[i] += s->proj[i];
         /* cross-attention over this sequence's own T encoder frames */
-        aedo_layernorm(s->x, lw->ln2_g, lw->ln2_b, d, eps, s->h);
+        norm_rows(cfg, s->x, lw->ln2_g, lw->ln2_b, d, eps, s->h);
         aedo_linear(s->h, lw->w_cq, lw->b_cq, d, d, s->qkv);
         for (int hd = 0; hd < H; ++hd)
             aedo_attend(s->qkv + hd * dh, s->Kc[l] + hd * dh, s->Vc[l] + hd * dh, s->T, dh, d,
@@ -272,14 +289,14 @@ static void seq_step(const aedo_config *cfg, const aedo_weights *w, seq_state *s
         aedo_linear(s->att, lw->w_co, lw->b_co, d, d, s->proj);
         for (int i = 0; i < d; ++i) s->x[i] += s->proj[i];
         /* feed-forward */
-        aedo_layernorm(s->x, lw->ln3_g, lw->ln3_b, d, eps, s->h);
+        norm_rows(cfg, s->x, lw->ln3_g, lw->ln3_b, d, eps, s->h);
         aedo_linear(s->h, lw->w_ff1, lw->b_ff1, d, F, s->ffn);
         for (int i = 0; i < F; ++i)
             if (s->ffn[i] < 0.0) s->ffn[i] = 0.0;
         aedo_linear(s->ffn, lw->w_ff2, lw->b_ff2, F, d, s->proj);
         for (int i = 0; i < d; ++i) s->x[i] += s->proj[i];
     }
-    aedo_layernorm(s->x, w->lnf_g, w->lnf_b, d, eps, s->h);
+    norm_rows(cfg, s->x, w->lnf_g, w->lnf_b, d, eps, s->h);
     aedo_linear(s->h, w->w_out, w->b_out, d, cfg->vocab, logits);
     s->len = pos + 1;
 }
@@ -455,7 +472,7 @@ int aedo_forward_full(const aedo_config *cfg, const aedo_weights *w,
         for (int l = 0; l < cfg->n_layers; ++l) {
             const aedo_layer *lw = &w->layers[l];
             for (int s = 0; s < S; ++s) {
-                aedo_layernorm(X + (size_t)s * d, lw->ln1_g, lw->ln1_b, d, eps, Hn + (size_t)s * d);
+                norm_rows(cfg, X + (size_t)s * d, lw->ln1_g, lw->ln1_b, d, eps, Hn + (size_t)s * d);
                 aedo_linear(Hn + (size_t)s * d, lw->w_qkv, lw->b_qkv, d, 3 * d, row3);
                 if (cfg->kv_fp8) store_as_fp8(row3 + d, 2 * d);
                 memcpy(Q + (size_t)s * d, row3, sizeof(double) * (size_t)d);
@@ -481,7 +498,7 @@ int aedo_forward_full(const aedo_config *cfg, const aedo_weights *w,
                 }
             }
             for (int s = 0; s < S; ++s) {
-                aedo_layernorm(X + (size_t)s * d, lw->ln2_g, lw->ln2_b, d, eps, Hn + (size_t)s * d);
+                norm_rows(cfg, X + (size_t)s * d, lw->ln2_g, lw->ln2_b, d, eps, Hn + (size_t)s * d);
                 aedo_linear(Hn + (size_t)s * d, lw->w_cq, lw->b_cq, d, d, Q + (size_t)s * d);
             }
             for (int hd = 0; hd < H; ++hd)
@@ -491,7 +508,7 @@ int aedo_forward_full(const aedo_config *cfg, const aedo_weights *w,
                 for (int i = 0; i < d; ++i) X[(size_t)s * d + i] += rowd[i];
             }
             for (int s = 0; s < S; ++s) {
-                aedo_layernorm(X + (size_t)s * d, lw->ln3_g, lw->ln3_b, d, eps, Hn + (size_t)s * d);
+                norm_rows(cfg, X + (size_t)s * d, lw->ln3_g, lw->ln3_b, d, eps, Hn + (size_t)s * d);
                 aedo_linear(Hn + (size_t)s * d, lw->w_ff1, lw->b_ff1, d, F, rowF);
                 for (int i = 0; i < F; ++i)
                     if (rowF[i] < 0.0) rowF[i] = 0.0;
@@ -505,7 +522,7 @@ int aedo_forward_full(const aedo_config *cfg, const aedo_weights *w,
                 memset(out, 0, sizeof(double) * (size_t)V);
                 continue;
             }
-            aedo_layernorm(X + (size_t)s * d, w->lnf_g, w->lnf_b, d, eps, rowd);
+            norm_rows(cfg, X + (size_t)s * d, w->lnf_g, w->lnf_b, d, eps, rowd);
             aedo_linear(rowd, w->w_out, w->b_out, d, V, out);
         }
         free(X); free(Hn); free(Q); free(K); free(Vv); free(A); free(Kc); free(Vc);

@@ -41,6 +41,7 @@ typedef struct aedo_config {
     int32_t pad_id;   /* written after a sequence has finished */
     float ln_eps, emb_scale;
     int32_t kv_fp8;   /* nonzero: attention keys and values are stored as 8-bit E4M3 codes (see below) */
+    int32_t norm_type; /* 0: LayerNorm in every place the model normalises; 1: RMSNorm (aedo_rmsnorm) instead */
 } aedo_config;
 
 typedef struct aedo_layer {
@@ -59,6 +60,9 @@ typedef struct aedo_weights {
 
 /* y = g * (z - mean) / sqrt(biased_var + eps) + b over n elements. */
 void aedo_layernorm(const double *z, const float *g, const float *b, int n, double eps, double *y);
+/* Root-mean-square normalisation (Zhang and Sennrich, 2019: the mean is not subtracted):
+ * y = g * z / sqrt(mean(z^2) + eps) + b over n elements; b may be NULL (no shift). */
+void aedo_rmsnorm(const double *z, const float *g, const float *b, int n, double eps, double *y);
 /* y[o] = bias[o] + sum_i W[o, i] * x[i]. */
 void aedo_linear(const double *x, const float *W, const float *bias, int n_in, int n_out, double *y);
 /* p = exp(a - max a) / sum. */
@@ -75,10 +79,11 @@ int32_t aedo_argmax(const double *a, int n);
  * steps stream).  Format: E4M3 of the OCP 8-bit floating point specification
  * (OFP8): 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals at
  * exponent field 0, no infinities, S.1111.111 is NaN, largest magnitude 448.
- * Encoding takes the value as a float (the precision the product's kernels
- * hold it in), rounds to the nearest code, ties to the even code, and
- * saturates: anything beyond 448 becomes +-448.  With cfg.kv_fp8 set, every
- * key / value element is replaced by decode(encode(.)) at the moment it is
+ * Encoding first rounds the (double) value to float32, then rounds that to
+ * the nearest code, ties to the even code, and saturates (the float32 step is
+ * part of this definition; it differs from rounding the double directly only
+ * for values within 2^-24 relative of the midpoint of two codes): anything
+ * beyond 448 becomes +-448.  With cfg.kv_fp8 set, every key / value element is replaced by decode(encode(.)) at the moment it is
  * cached; nothing else changes. */
 uint8_t aedo_fp8_e4m3_encode(float x);
 double aedo_fp8_e4m3_decode(uint8_t code);

@@ -30,7 +30,7 @@ class _Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
                  "max_positions", "eos_id", "pad_id")] + \
-               [("ln_eps", C.c_float), ("emb_scale", C.c_float), ("kv_fp8", C.c_int32)]
+               [("ln_eps", C.c_float), ("emb_scale", C.c_float), ("kv_fp8", C.c_int32), ("norm_type", C.c_int32)]
 
 
 class _Layer(C.Structure):
@@ -53,6 +53,8 @@ def lib():
         _lib = C.CDLL(path)
         _lib.aedo_layernorm.argtypes = [_f64p, _f32p, _f32p, C.c_int, C.c_double, _f64p]
         _lib.aedo_layernorm.restype = None
+        _lib.aedo_rmsnorm.argtypes = [_f64p, _f32p, _f32p, C.c_int, C.c_double, _f64p]
+        _lib.aedo_rmsnorm.restype = None
         _lib.aedo_linear.argtypes = [_f64p, _f32p, _f32p, C.c_int, C.c_int, _f64p]
         _lib.aedo_linear.restype = None
         _lib.aedo_softmax.argtypes = [_f64p, C.c_int, _f64p]
@@ -125,6 +127,7 @@ class Model:
         c.ln_eps = float(cfg.ln_eps)
         c.emb_scale = float(cfg.emb_scale)
         c.kv_fp8 = int(getattr(cfg, "kv_fp8", 0))
+        c.norm_type = int(getattr(cfg, "norm_type", 0))
         self.c_cfg = c
         layers = (_Layer * cfg.n_layers)()
         for i, lw in enumerate(weights["layers"]):
@@ -215,6 +218,14 @@ def layernorm(z, g, b, eps):
     z, g, b = _f64(z), _f32(g), _f32(b)
     y = np.zeros_like(z)
     lib().aedo_layernorm(_p64(z), _p32(g), _p32(b), z.size, float(eps), _p64(y))
+    return y
+
+
+def rmsnorm(z, g, b, eps):
+    z, g = _f64(z), _f32(g)
+    b = None if b is None else _f32(b)
+    y = np.zeros_like(z)
+    lib().aedo_rmsnorm(_p64(z), _p32(g), _p32(b), z.size, float(eps), _p64(y))
     return y
 
 

@@ -87,7 +87,7 @@ aed_status check_config(const aed_config* c, std::string& err) {
     if (c->kv_pages < 0) return bad("kv_pages < 0");
     if (!(c->ln_eps > 0.f)) return bad("ln_eps must be > 0");
     if (c->eos_id >= c->vocab || c->pad_id < 0) return bad("eos_id / pad_id out of range");
-    if (c->norm_type != 0) return unsup("only LayerNorm (norm_type 0) is built");
+    if (c->norm_type != 0 && c->norm_type != 1) return bad("norm_type must be 0 (LayerNorm) or 1 (RMSNorm)");
     if (c->page_size != kPage) return unsup("page_size must be 16");
     if (c->head_dim != 64 && c->head_dim != 128) return unsup("head_dim must be 64 or 128");
     if (c->d_model % 256 != 0 || c->d_model > 1024) return unsup("d_model must be a multiple of 256, at most 1024");
@@ -299,6 +299,7 @@ GemmArgs gemm_base(const aed_decoder* d, int layer) {
     g.head_dim = d->cfg.head_dim;
     g.d_model = d->cfg.d_model;
     g.kv_fp8 = d->cfg.kv_fp8;
+    g.rms = d->cfg.norm_type == 1;
     g.w_nt = d->w_nt && layer >= d->resident_layers;
     return g;
 }
@@ -491,6 +492,7 @@ hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* st
         sa.stats = stats_buf(d, 0);
         sa.mu_hat = shift_buf(d, 1);  // read as the shift of version 0 by the first product
         sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+        sa.rms = d->cfg.norm_type == 1;
     }
     e = launch_embed(d->dt, d->act_at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
                      d->cfg.max_positions, d->cfg.emb_scale, sa, d->stream);
@@ -504,12 +506,13 @@ hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* st
 
 aed_status check_weights(const aed_config* c, const aed_weights* w) {
     if (!w) return fail(nullptr, AED_EINVAL, "weights is NULL");
-    if (!w->tok_emb || !w->pos_emb || !w->lnf_g || !w->lnf_b || !w->w_out || !w->layers)
+    const bool need_shift = c->norm_type == 0;  // RMSNorm: a missing shift vector is zero
+    if (!w->tok_emb || !w->pos_emb || !w->lnf_g || (need_shift && !w->lnf_b) || !w->w_out || !w->layers)
         return fail(nullptr, AED_EINVAL, "a required top-level weight pointer is NULL");
     for (int l = 0; l < c->n_layers; ++l) {
         const aed_layer_weights& x = w->layers[l];
-        if (!x.ln1_g || !x.ln1_b || !x.w_qkv || !x.w_o || !x.ln2_g || !x.ln2_b || !x.w_cq || !x.w_ckv || !x.w_co ||
-            !x.ln3_g || !x.ln3_b || !x.w_ff1 || !x.w_ff2)
+        if (!x.ln1_g || !x.w_qkv || !x.w_o || !x.ln2_g || !x.w_cq || !x.w_ckv || !x.w_co || !x.ln3_g || !x.w_ff1 ||
+            !x.w_ff2 || (need_shift && (!x.ln1_b || !x.ln2_b || !x.ln3_b)))
             return fail(nullptr, AED_EINVAL, "layer %d: a required weight pointer is NULL", l);
     }
     return AED_OK;
@@ -674,6 +677,7 @@ aed_status prefill_pass(aed_decoder* d, const std::vector<int>& prompt_host, int
             sa.stats = stats_buf(d, 0);
             sa.mu_hat = shift_buf(d, 1);
             sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+            sa.rms = d->cfg.norm_type == 1;
         }
         hipError_t e = launch_embed(d->dt, d->act_at<float>(d->lay.x), d->w.tok_emb, d->w.pos_emb, st, d->cfg.d_model,
                                     d->cfg.max_positions, d->cfg.emb_scale, sa, d->stream);

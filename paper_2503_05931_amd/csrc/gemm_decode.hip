@@ -185,7 +185,8 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         for (int i = 0; i < kMaxLnBlocks; ++i)
             if (i < nblk) {
                 gam_f[i] = load_frag_rm(G + (i * 4 + wave) * 64 + g * 16);
-                bet_f[i] = load_frag_rm(Bt + (i * 4 + wave) * 64 + g * 16);
+                if (Bt) bet_f[i] = load_frag_rm(Bt + (i * 4 + wave) * 64 + g * 16);
+                else zero_frag(bet_f[i]);
             }
         // row mean
         float mean[MT], rstd[MT];
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             int i = mt * 16 + r;
-            mean[mt] = (red[0][0][i] + red[0][1][i] + red[0][2][i] + red[0][3][i]) / (float)K;
+            mean[mt] = a.rms ? 0.f : (red[0][0][i] + red[0][1][i] + red[0][2][i] + red[0][3][i]) / (float)K;
             float s = 0.f;
 #pragma unroll
             for (int b = 0; b < kMaxLnBlocks; ++b)
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         if constexpr (LNS) {
             float mu, m2;
             row_stats(mt * 16 + (l & 15), mu, m2);
-            const float rstd = 1.0f / sqrtf(m2 / (float)K + a.ln_eps), shift = mu - e_mu[j];
+            const float rstd = fold_norm(a.rms, (float)K, a.ln_eps, m2, mu), shift = mu - e_mu[j];
             s = (s - shift * e_aux[j]) * rstd + e_bias[j];
             if constexpr (EPI == EPI_QKV) store_qkv(m, n, s, e_kv[j]);
             else gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
 template <typename T>
 __global__ __launch_bounds__(256) void layernorm_frag_kernel(const char* __restrict__ X, const T* __restrict__ G,
                                                              const T* __restrict__ Bt, char* __restrict__ Hout, int M,
-                                                             int K, float eps) {
+                                                             int K, float eps, int rms) {
     constexpr int ES = sizeof(T);
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(256) void layernorm_frag_kernel(const char* __restr
     for (int e = 0; e < 16; ++e) s += x[e];
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-    const float mean = s / (float)K;
+    const float mean = rms ? 0.f : s / (float)K;  // RMSNorm: no mean subtraction
     float m2 = 0.f;
     if (live) {
 #pragma unroll
@@ -388,7 +389,12 @@ __global__ __launch_bounds__(256) void layernorm_frag_kernel(const char* __restr
     const int k0 = lane * 16;
     float gam[16], bet[16], y[16];
     unpack_frag(load_frag_rm(G + k0), gam);
-    unpack_frag(load_frag_rm(Bt + k0), bet);
+    if (Bt) {
+        unpack_frag(load_frag_rm(Bt + k0), bet);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bet[e] = 0.f;
+    }
 #pragma unroll
     for (int e = 0; e < 16; ++e) y[e] = (x[e] - mean) * rstd * gam[e] + bet[e];
     Frag16<T> f;
@@ -468,7 +474,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
         if (!a.ln_scratch) return hipErrorInvalidValue;
         hipLaunchKernelGGL(layernorm_frag_kernel<T>, dim3((a.M + 3) / 4), dim3(256), 0, s,
                            static_cast<const char*>(a.A), static_cast<const T*>(a.ln_g), static_cast<const T*>(a.ln_b),
-                           static_cast<char*>(a.ln_scratch), a.M, a.K, a.ln_eps);
+                           static_cast<char*>(a.ln_scratch), a.M, a.K, a.ln_eps, a.rms);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         a.A = a.ln_scratch;
@@ -524,7 +530,7 @@ __global__ __launch_bounds__(256) void fold_ln_kernel(const T* __restrict__ W, c
     for (int k = lane; k < K; k += 64) {
         const float w = (float)W[(size_t)n * K + k];
         s1 += w * (float)g[k];
-        s2 += w * (float)b[k];
+        if (b) s2 += w * (float)b[k];
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {

@@ -209,9 +209,10 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
             for (int mt = 0; mt < 2; ++mt) {
                 const int rl = wm * 64 + mt * 32 + r32, m = tm * kBM + rl;
                 const float a0 = row_stat[0][0][rl], a1 = row_stat[0][1][rl];
-                const float mu = 0.5f * (a0 + a1), d0 = a0 - mu, d1 = a1 - mu;
+                float mu = 0.5f * (a0 + a1);
+                const float d0 = a0 - mu, d1 = a1 - mu;
                 const float m2 = row_stat[1][0][rl] + row_stat[1][1][rl] + stat_n * (d0 * d0 + d1 * d1);
-                rstd[mt] = 1.0f / sqrtf(m2 / (float)K + a.ln_eps);
+                rstd[mt] = fold_norm(a.rms, (float)K, a.ln_eps, m2, mu);
                 shift[mt] = m < a.M ? mu - a.mu_hat_in[m] : 0.f;
                 if (tn == 0 && wn == 0 && hh == 0 && m < a.M) a.mu_hat_out[m] = mu;  // for the next residual update
             }

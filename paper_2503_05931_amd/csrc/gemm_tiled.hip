@@ -163,9 +163,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
         for (int i = 0; i < WM; ++i) {
             const int rl = (wm * WM + i) * 16 + r;
             const float a0 = row_stat[0][0][rl], a1 = row_stat[0][1][rl];
-            const float mu = 0.5f * (a0 + a1), d0 = a0 - mu, d1 = a1 - mu;
+            float mu = 0.5f * (a0 + a1);
+            const float d0 = a0 - mu, d1 = a1 - mu;
             const float m2 = row_stat[1][0][rl] + row_stat[1][1][rl] + stat_n * (d0 * d0 + d1 * d1);
-            rstd[i] = 1.0f / sqrtf(m2 / (float)K + a.ln_eps);
+            rstd[i] = fold_norm(a.rms, (float)K, a.ln_eps, m2, mu);
             shift[i] = m0 + rl < a.M ? mu - a.mu_hat_in[m0 + rl] : 0.f;
             if (n0 == 0 && wn == 0 && g == 0 && m0 + rl < a.M) a.mu_hat_out[m0 + rl] = mu;  // for the next residual update
         }

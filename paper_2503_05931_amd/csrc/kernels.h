@@ -59,6 +59,8 @@ struct GemmArgs {
     const void* shadow_g;    // EPI_RESID_S: T [N]
     int stat_tiles, m_stride;
     int kv_fp8;              // EPI_QKV / EPI_CROSSKV: the caches hold 8-bit E4M3 codes instead of T
+    int rms;                 // the normalisation is RMSNorm (no mean subtraction; ln_b may be null) instead of LayerNorm:
+                             // PRO_LN normalises that way, PRO_LNS reads the statistics that way (see fold_norm)
     int w_nt;                // streaming kernel: load W with the non-temporal hint (weights that are not expected to
                              // survive in the caches until the next step anyway, and should not push other data out)
 };
@@ -128,6 +130,7 @@ struct ShadowArgs {
     float2* stats;      // [d / 16][m_stride]: mean and sum of squared deviations of every 16-column tile
     float* mu_hat;      // [B] row means (the shadow's shift)
     int m_stride;
+    int rms;            // RMSNorm: the shadow is x * g and the shift 0
 };
 // x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]   (x in fragment order); d_model <= 1024
 hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,

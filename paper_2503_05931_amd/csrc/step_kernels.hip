@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void embed_kernel(float* __restrict__ x, const
     for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
     if ((tid & 63) == 0) wsum[tid >> 6] = s;
     __syncthreads();
-    const float mean = (wsum[0] + wsum[1] + wsum[2] + wsum[3]) / (float)d;
+    const float mean = sh.rms ? 0.f : (wsum[0] + wsum[1] + wsum[2] + wsum[3]) / (float)d;  // RMSNorm: no shift
     float ts = t4;
     ts += __shfl_xor(ts, 1);
     ts += __shfl_xor(ts, 2);

@@ -63,7 +63,7 @@ def test_workspace_bytes_counts_the_caches(lib):
     ("kv_pages", -1, binding.AED_EINVAL),
     ("kv_fp8", 2, binding.AED_EINVAL),
     ("prefill_rows", -1, binding.AED_EINVAL),
-    ("norm_type", 1, binding.AED_EUNSUPPORTED),
+    ("norm_type", 2, binding.AED_EINVAL),
     ("page_size", 32, binding.AED_EUNSUPPORTED),
     ("d_ffn", 1000, binding.AED_EUNSUPPORTED),
     ("vocab", 1000, binding.AED_EUNSUPPORTED),

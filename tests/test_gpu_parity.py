@@ -112,16 +112,18 @@ def test_teacher_forced_shapes(torch_cuda, oracle, dtype, d_model, n_heads, head
     dec.close()
 
 
-@pytest.mark.parametrize("d_model,n_heads,head_dim,batch", [
-    (512, 4, 128, 1750),   # QKV product: 14 x 12 tiles of 128 x 128, K = 512 -> direct-to-LDS 128-tile kernel
-    (256, 4, 64, 3500),    # QKV product: 28 x 6 tiles, K = 256 -> register-staged 128-tile kernel
+@pytest.mark.parametrize("d_model,n_heads,head_dim,batch,norm_type", [
+    (512, 4, 128, 1750, 0),   # QKV product: 14 x 12 tiles of 128 x 128, K = 512 -> direct-to-LDS 128-tile kernel
+    (256, 4, 64, 3500, 0),    # QKV product: 28 x 6 tiles, K = 256 -> register-staged 128-tile kernel
+    (512, 4, 128, 1750, 1),   # the same two kernels with RMSNorm folded around the products
+    (256, 4, 64, 3500, 1),
 ])
-def test_very_large_batches_tiled_projections(torch_cuda, oracle, d_model, n_heads, head_dim, batch):
-    """Batches large enough for the 128 x 128 tiled kernels to take the QKV product, LayerNorm folded around it
-    (ragged last row tile); a few teacher-forced steps against the oracle."""
+def test_very_large_batches_tiled_projections(torch_cuda, oracle, d_model, n_heads, head_dim, batch, norm_type):
+    """Batches large enough for the 128 x 128 tiled kernels to take the QKV product, the normalisation folded
+    around it (ragged last row tile); a few teacher-forced steps against the oracle."""
     from tests import gpu_util as G
     enc_lens = [1 + (5 * i) % 7 for i in range(batch)]
-    wl = unit_workload("bf16", d_model, n_heads, head_dim, enc_lens, seed=batch, max_new=8)
+    wl = unit_workload("bf16", d_model, n_heads, head_dim, enc_lens, seed=batch, max_new=8, norm_type=norm_type)
     toks = random_tokens(wl.cfg, batch, 4, 6)
     ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
     dec = G.make_decoder(wl)
@@ -519,4 +521,51 @@ def test_bf16_logits_through_finished_and_forced_eos(torch_cuda, oracle):
                 assert lens[b] == n
     assert compared >= 30
     print(f"bf16 greedy logits with finished rows in the batch: {compared} rows compared, max |dlogit| = {worst:.3e}")
+    dec.close()
+
+
+# ---------------------------------------------------------------- RMSNorm variant (norm_type = 1)
+@pytest.mark.parametrize("dtype,d_model,n_heads,head_dim,enc_lens,shifts", [
+    ("fp32", 256, 4, 64, [1, 15, 16, 17, 63, 64, 65, 130], True),
+    ("bf16", 256, 4, 64, [1, 15, 16, 17, 63, 64, 65, 130], True),
+    ("bf16", 1024, 8, 128, [257, 1, 64], False),               # no shift vectors (NULL pointers)
+    ("fp32", 256, 4, 64, [1 + (11 * i) % 60 for i in range(131)], False),   # the normalisation as its own launch
+    ("bf16", 512, 4, 128, [3 + (5 * i) % 40 for i in range(300)], True),    # large tiles, folded normalisation
+    ("bf16", 256, 4, 64, [2 + (3 * i) % 25 for i in range(530)], True),     # LDS-tiled kernels
+])
+def test_rmsnorm_teacher_forced(torch_cuda, oracle, dtype, d_model, n_heads, head_dim, enc_lens, shifts):
+    """Every normalisation of the decoder as RMSNorm (no mean subtraction): teacher-forced logits against the
+    oracle in both modes, embeddings shifted so that the rows' means are far from zero (a LayerNorm in any of the
+    places would give other logits), and the greedy path with prompt prefill."""
+    from tests import gpu_util as G
+    torch = torch_cuda
+    wl = unit_workload(dtype, d_model, n_heads, head_dim, enc_lens, seed=len(enc_lens) + d_model + 1, norm_type=1,
+                       max_new=28)
+    w = wl.weights
+    w["pos_emb"] = W.bf16_round((w["pos_emb"] + 0.05).astype(np.float32)) if dtype == "bf16" else (w["pos_emb"] + 0.05).astype(np.float32)
+    if not shifts:
+        w["lnf_b"] = None
+        for l in w["layers"]:
+            l["ln1_b"] = l["ln2_b"] = l["ln3_b"] = None
+    S = 20 if len(enc_lens) < 100 else 6
+    toks = random_tokens(wl.cfg, len(enc_lens), S, 5)
+    m = oracle.Model(wl.cfg, w)
+    ref = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    import copy
+    cfg_ln = copy.copy(wl.cfg)
+    cfg_ln.norm_type = 0
+    if shifts:
+        assert np.abs(oracle.Model(cfg_ln, w).decode_forced(wl.enc[:int(wl.enc_lens[0])], wl.enc_lens[:1], toks[:1]) - ref[:1]).max() > 10 * G.TOL[dtype]
+    dec = G.make_decoder(wl, prefill_rows=16 * ((len(enc_lens) + 15) // 16) if len(enc_lens) < 100 else 0)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL[dtype])
+    print(f"RMSNorm {dtype} d={d_model} B={len(enc_lens)}: max |dlogit| = {err:.2e}, near ties {near}")
+    if len(enc_lens) < 100:
+        ref_t, ref_l, ref_logits = m.greedy_decode(wl.enc, wl.enc_lens, wl.prompt, 12, want_logits=True)
+        dec.aed_cross_kv_precompute(dec.to_device(wl.enc), wl.enc_lens)
+        out, lens = dec.aed_greedy_decode(torch.from_numpy(wl.prompt).to(dec.device), 12)
+        out = out.cpu().numpy()
+        first = G.first_near_tie(ref_logits, G.TOL[dtype])
+        for b in range(len(enc_lens)):
+            assert (out[b, :first[b]] == ref_t[b, :first[b]]).all()
     dec.close()

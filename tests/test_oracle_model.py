@@ -290,3 +290,84 @@ def test_self_kv_of_the_first_layer_is_the_projection_of_the_embedding(oracle):
     K1, V1 = m.self_kv(1, wl.enc[:wl.enc_lens[0]], toks)
     K1s, V1s = m.self_kv(1, wl.enc[:wl.enc_lens[0]], toks[:3])
     assert np.array_equal(K1[:3], K1s) and np.array_equal(V1[:3], V1s)
+
+
+# ---- RMSNorm variant (norm_type = 1) ----
+def _torch_decoder_rms(cfg, w):
+    """torch's pre-norm decoder with every LayerNorm module replaced by torch.nn.RMSNorm (gain only)."""
+    dec = _torch_decoder(cfg, w)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+
+    def rms(gain):
+        mod = torch.nn.RMSNorm(cfg.d_model, eps=cfg.ln_eps).double()
+        with torch.no_grad():
+            mod.weight.copy_(t(gain))
+        return mod
+
+    for l, lw in zip(dec.layers, w["layers"]):
+        l.norm1, l.norm2, l.norm3 = rms(lw["ln1_g"]), rms(lw["ln2_g"]), rms(lw["ln3_g"])
+    dec.norm = rms(w["lnf_g"])
+    return dec.eval()
+
+
+def _without_norm_shifts(w):
+    w = dict(w)
+    w["lnf_b"] = None
+    w["layers"] = [dict(l, ln1_b=None, ln2_b=None, ln3_b=None) for l in w["layers"]]
+    return w
+
+
+def test_rmsnorm_model_matches_torch_decoder_with_rmsnorm_modules(oracle):
+    wl = small_workload(seed=5, enc_lens=(6, 3, 10, 1), norm_type=1)
+    cfg = wl.cfg
+    w = _without_norm_shifts(wl.weights)
+    B, S = 4, 8
+    toks = random_tokens(cfg, B, S, 15)
+    mine = oracle.Model(cfg, w).decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = _torch_decoder_rms(cfg, wl.weights)
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    x0 = cfg.emb_scale * t(w["tok_emb"])[torch.from_numpy(toks).long()] + t(w["pos_emb"])[:S][None]
+    mem = t(pad_enc(wl))
+    kpm = torch.arange(mem.shape[1])[None, :] >= torch.from_numpy(wl.enc_lens)[:, None]
+    causal = torch.triu(torch.ones(S, S, dtype=torch.bool), diagonal=1)
+    with torch.no_grad():
+        hid = dec(x0, mem, tgt_mask=causal, memory_key_padding_mask=kpm)
+        ref = (hid @ t(w["w_out"]).T + t(w["b_out"])).numpy()
+    assert np.abs(mine - ref).max() < 1e-9
+    # and it is not the LayerNorm model
+    wl_ln = small_workload(seed=5, enc_lens=(6, 3, 10, 1))
+    other = oracle.Model(wl_ln.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
+    assert np.abs(other - mine).max() > 1e-2
+
+
+def test_rmsnorm_incremental_equals_full_forward_and_padding(oracle):
+    wl = small_workload(seed=6, norm_type=1)
+    m = oracle.Model(wl.cfg, wl.weights)   # with shift vectors
+    S = 7
+    toks = random_tokens(wl.cfg, 3, S, 17)
+    inc = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    full = m.forward_full(pad_enc(wl, fill=np.nan), wl.enc_lens, toks, np.full(3, S, np.int32))
+    assert np.abs(inc - full).max() < 1e-10
+    # the shift vectors are in use: dropping them changes the logits
+    inc0 = oracle.Model(wl.cfg, _without_norm_shifts(wl.weights)).decode_forced(wl.enc, wl.enc_lens, toks)
+    assert np.abs(inc0 - inc).max() > 1e-3
+
+
+def test_rmsnorm_equals_layernorm_while_every_normalised_row_has_zero_mean(oracle):
+    """If the embeddings are zero-mean rows and every residual update is (output matrices and biases with zero
+    column means), every row that is ever normalised has mean zero, where the two normalisations agree: the
+    RMSNorm model then gives the LayerNorm model's logits (which torch's decoder pins)."""
+    wl = small_workload(seed=7)
+    w = wl.weights
+    for k in ("tok_emb", "pos_emb"):
+        w[k] = (w[k] - w[k].mean(axis=1, keepdims=True)).astype(np.float32)
+    for l in w["layers"]:
+        for k in ("w_o", "w_co", "w_ff2"):
+            l[k] = (l[k] - l[k].mean(axis=0, keepdims=True)).astype(np.float32)
+        for k in ("b_o", "b_co", "b_ff2"):
+            l[k] = (l[k] - l[k].mean()).astype(np.float32)
+    toks = random_tokens(wl.cfg, 3, 6, 19)
+    ln_logits = oracle.Model(wl.cfg, w).decode_forced(wl.enc, wl.enc_lens, toks)
+    cfg_rms = small_cfg(norm_type=1)
+    rms_logits = oracle.Model(cfg_rms, w).decode_forced(wl.enc, wl.enc_lens, toks)
+    assert np.abs(ln_logits - rms_logits).max() < 1e-5   # float32 weights: the means are zero to ~1e-8 only

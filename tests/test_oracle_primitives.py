@@ -130,3 +130,41 @@ def test_argmax_lowest_index_on_ties(oracle):
     assert oracle.argmax(np.array([1.0, 3.0, 3.0, 2.0])) == 1
     assert oracle.argmax(np.array([5.0, 5.0, 5.0])) == 0
     assert oracle.argmax(np.array([-2.0, -1.0])) == 1
+
+
+def test_rmsnorm_closed_forms(oracle):
+    """Root-mean-square normalisation (Zhang and Sennrich 2019): no mean subtraction."""
+    g1, b0 = np.ones(2, np.float32), np.zeros(2, np.float32)
+    # [3, 4]: mean square 12.5
+    y = oracle.rmsnorm(np.array([3.0, 4.0]), g1, None, 0.0)
+    assert np.allclose(y, np.array([3.0, 4.0]) / math.sqrt(12.5), atol=1e-15)
+    # eps sits inside the root, next to the mean square
+    y = oracle.rmsnorm(np.array([3.0, 4.0]), g1, None, 3.5)
+    assert np.allclose(y, np.array([3.0, 4.0]) / 4.0, atol=1e-15)
+    # scale invariance at eps = 0, and none under a shift of the input (a LayerNorm would not notice the shift)
+    rng = np.random.default_rng(5)
+    z = rng.standard_normal(37)
+    g = rng.standard_normal(37).astype(np.float32)
+    b = rng.standard_normal(37).astype(np.float32)
+    assert np.allclose(oracle.rmsnorm(7.5 * z, g, b, 0.0), oracle.rmsnorm(z, g, b, 0.0), atol=1e-13)
+    assert np.abs(oracle.rmsnorm(z + 2.0, g, b, 1e-5) - oracle.rmsnorm(z, g, b, 1e-5)).max() > 0.1
+    assert np.allclose(oracle.layernorm(z + 2.0, g, b, 1e-5), oracle.layernorm(z, g, b, 1e-5), atol=1e-12)
+    # on a zero-mean row it equals LayerNorm (biased variance = mean square)
+    z0 = z - z.mean()
+    assert np.allclose(oracle.rmsnorm(z0, g, b, 1e-5), oracle.layernorm(z0, g, b, 1e-5), atol=1e-13)
+    # gain multiplies, shift adds, a missing shift is zero
+    y0 = oracle.rmsnorm(z, np.ones(37, np.float32), None, 1e-5)
+    assert np.allclose(oracle.rmsnorm(z, g, b, 1e-5), y0 * g.astype(np.float64) + b.astype(np.float64), atol=1e-14)
+    assert np.array_equal(oracle.rmsnorm(z, g, None, 1e-5), oracle.rmsnorm(z, g, np.zeros(37, np.float32), 1e-5))
+    # output has mean square n / (n + eps * n / ms) -> 1 for eps -> 0
+    assert abs((y0 ** 2).mean() - (z ** 2).mean() / ((z ** 2).mean() + 1e-5)) < 1e-14
+
+
+def test_rmsnorm_matches_torch(oracle):
+    import torch
+    rng = np.random.default_rng(6)
+    for n in (8, 33, 256):
+        z = rng.standard_normal(n) * 3 + 1
+        g = rng.standard_normal(n).astype(np.float32)
+        ref = torch.nn.functional.rms_norm(torch.from_numpy(z), (n,), torch.from_numpy(g.astype(np.float64)), 1e-5).numpy()
+        assert np.abs(oracle.rmsnorm(z, g, None, 1e-5) - ref).max() < 1e-13
