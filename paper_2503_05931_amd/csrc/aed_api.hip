@@ -374,8 +374,8 @@ hipError_t k_self_attn(aed_decoder* d, int l) {
     return launch_attn_self(d->dt, a, d->stream);
 }
 
-// x += A . W^T + bias; next_g: gain of the LayerNorm that reads x next (its shadow is written with it)
-hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const void* bias, int K, const void* next_g) {
+// x += A . W^T + bias
+hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const void* bias, int K) {
     GemmArgs g = gemm_base(d, l);
     g.A = A; g.W = W; g.bias = bias;
     g.N = d->cfg.d_model; g.K = K;
@@ -384,7 +384,6 @@ hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const vo
         g.stats_out = stats_buf(d, d->x_par ^ 1);
         g.mu_hat_in = shift_buf(d, d->x_par);  // mean of the rows before the update, left by the product that read them
         g.shadow_out = d->act + d->lay.x_shadow;
-        g.shadow_g = next_g;
         g.stat_tiles = d->cfg.d_model / 16;
         g.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
         d->x_par ^= 1;
@@ -467,14 +466,13 @@ hipError_t k_class(aed_decoder* d, int cls, int l) {
     switch (cls) {
         case AED_K_LN_QKV: return k_ln_qkv(d, l);
         case AED_K_SELF_ATTN: return k_self_attn(d, l);
-        case AED_K_SELF_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model, w.ln2_g);
+        case AED_K_SELF_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model);
         case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
         case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
-        case AED_K_CROSS_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model, w.ln3_g);
+        case AED_K_CROSS_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model);
         case AED_K_LN_FFN1: return k_ln_ffn1(d, l);
         case AED_K_FFN2:
-            return k_resid(d, l, d->act + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn,
-                           l + 1 < d->cfg.n_layers ? d->layers[l + 1].ln1_g : d->w.lnf_g);
+            return k_resid(d, l, d->act + d->lay.ffn_h, d->fw[l].w_ff2, w.b_ff2, d->cfg.d_ffn);
         case AED_K_CROSS_KV: return k_cross_kv(d, l, d->total_enc, nullptr);
         default: return hipErrorInvalidValue;
     }
@@ -488,7 +486,6 @@ hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* st
     if (folded_ln(d)) {
         d->x_par = 0;
         sa.shadow = d->act + d->lay.x_shadow;
-        sa.g = d->layers[0].ln1_g;
         sa.stats = stats_buf(d, 0);
         sa.mu_hat = shift_buf(d, 1);  // read as the shift of version 0 by the first product
         sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
@@ -673,8 +670,7 @@ aed_status prefill_pass(aed_decoder* d, const std::vector<int>& prompt_host, int
         if (folded_ln(d)) {
             d->x_par = 0;
             sa.shadow = d->act + d->lay.x_shadow;
-            sa.g = d->layers[0].ln1_g;
-            sa.stats = stats_buf(d, 0);
+                sa.stats = stats_buf(d, 0);
             sa.mu_hat = shift_buf(d, 1);
             sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
             sa.rms = d->cfg.norm_type == 1;
@@ -784,9 +780,11 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
     {
         char* p = d->ws + L.w_frag;
         const int dm = cfg->d_model, F = cfg->d_ffn;
-        auto put = [&](const void* src, int N, int K) -> const void* {
+        // bfloat16 mode: a matrix that follows a LayerNorm is stored with that LayerNorm's gain multiplied into its
+        // columns (the folded LayerNorm, kernels.h); float32 mode applies the gain to the rows instead
+        auto put = [&](const void* src, int N, int K, const void* gain = nullptr) -> const void* {
             void* dst = p;
-            if (e == hipSuccess) e = launch_reorder_weight(d->dt, src, dst, N, K, d->stream);
+            if (e == hipSuccess) e = launch_reorder_weight(d->dt, src, folded_ln(d) ? gain : nullptr, dst, N, K, d->stream);
             p += (size_t)N * K * d->esz;
             return dst;
         };
@@ -795,15 +793,15 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
         for (int l = 0; l < cfg->n_layers; ++l) {
             const aed_layer_weights& x = d->layers[l];
             aed_decoder::FragWeights& f = d->fw[l];
-            f.w_qkv = put(x.w_qkv, 3 * dm, dm);
+            f.w_qkv = put(x.w_qkv, 3 * dm, dm, x.ln1_g);
             f.w_o = put(x.w_o, dm, dm);
-            f.w_cq = put(x.w_cq, dm, dm);
+            f.w_cq = put(x.w_cq, dm, dm, x.ln2_g);
             f.w_ckv = put(x.w_ckv, 2 * dm, dm);
             f.w_co = put(x.w_co, dm, dm);
-            f.w_ff1 = put(x.w_ff1, F, dm);
+            f.w_ff1 = put(x.w_ff1, F, dm, x.ln3_g);
             f.w_ff2 = put(x.w_ff2, dm, F);
         }
-        d->fw_out = put(d->w.w_out, cfg->vocab, dm);
+        d->fw_out = put(d->w.w_out, cfg->vocab, dm, d->w.lnf_g);
         if (e != hipSuccess) return cleanup(e, "weight re-ordering");
     }
     if (folded_ln(d)) {  // W . g and W . b + bias of every product that follows a LayerNorm

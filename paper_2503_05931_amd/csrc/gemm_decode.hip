@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
     constexpr bool RS = EPI == EPI_RESID_S;      // residual update that also writes shadow and statistics
     constexpr bool RES = EPI == EPI_RESID || RS;
     const T* __restrict__ bias = static_cast<const T*>(a.bias);
-    f32x4 e_bias[EP], e_res[EP], e_aux[EP];  // e_aux: c1 (LNS) or the next LayerNorm's gain (RS)
+    f32x4 e_bias[EP], e_res[EP], e_aux[EP];  // e_aux: c1 (LNS)
     float e_mu[EP];                          // LNS: the shift this row's shadow was written with; RS: the row's
                                              // mean before the update = the shift its new shadow is written with
 #pragma unroll
@@ -83,7 +83,6 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         } else {
             e_bias[j] = (bias && live) ? load4(bias + n) : zero;
         }
-        if constexpr (RS) e_aux[j] = live ? load4(static_cast<const T*>(a.shadow_g) + n) : zero;
         if constexpr (LNS || RS) e_mu[j] = live ? a.mu_hat_in[m] : 0.f;
         if constexpr (RES)
             e_res[j] = live ? *reinterpret_cast<const f32x4*>(static_cast<const char*>(a.out) + frag_elem_off<4>(m, n, a.N))
@@ -315,8 +314,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             const float mu_old = e_mu[j];
             const f32x4 x = e_res[j] + s + e_bias[j];
             *reinterpret_cast<f32x4*>(static_cast<char*>(a.out) + frag_elem_off<4>(m, n, a.N)) = x;
-            store4(reinterpret_cast<T*>(static_cast<char*>(a.shadow_out) + frag_elem_off<ES>(m, n, a.N)),
-                   (x - mu_old) * e_aux[j]);
+            store4(reinterpret_cast<T*>(static_cast<char*>(a.shadow_out) + frag_elem_off<ES>(m, n, a.N)), x - mu_old);
             // this row's 16 columns of the tile sit in the four lanes l, l ^ 16, l ^ 32, l ^ 48
             float sum = (x[0] + x[1]) + (x[2] + x[3]);
             sum += __shfl_xor(sum, 16);
@@ -496,7 +494,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
             return hipErrorInvalidValue;
         }
         if (pro == PRO_T && epi == EPI_RESID_S) {
-            if (!a.stats_out || !a.mu_hat_in || !a.shadow_out || !a.shadow_g || a.stat_tiles < 4 ||
+            if (!a.stats_out || !a.mu_hat_in || !a.shadow_out || a.stat_tiles < 4 ||
                 a.stat_tiles % 4 != 0 || a.stat_tiles * 16 != a.N || a.stat_tiles > 4 * kMaxStatTilesPerGroup)
                 return hipErrorInvalidValue;
             return launch_tiles<T, PRO_T, EPI_RESID_S>(a, s);
@@ -529,7 +527,7 @@ __global__ __launch_bounds__(256) void fold_ln_kernel(const T* __restrict__ W, c
     float s1 = 0.f, s2 = 0.f;
     for (int k = lane; k < K; k += 64) {
         const float w = (float)W[(size_t)n * K + k];
-        s1 += w * (float)g[k];
+        s1 += to_f32(from_f32<T>(w * (float)g[k]));  // the column-scaled matrix as reorder_weight_kernel stores it
         if (b) s2 += w * (float)b[k];
     }
 #pragma unroll
@@ -558,18 +556,23 @@ hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b,
 }
 
 // ---------------------------------------------------------------- weight re-ordering
-// dst (fragment order) <- src (row-major [N, K]); one thread per 16-byte piece.
+// dst (fragment order) <- src (row-major [N, K]), columns scaled by gain (may be null); one thread per 16-byte piece.
 template <typename T>
-__global__ __launch_bounds__(256) void reorder_weight_kernel(const T* __restrict__ src, char* __restrict__ dst, int N,
-                                                             int K) {
+__global__ __launch_bounds__(256) void reorder_weight_kernel(const T* __restrict__ src, const T* __restrict__ gain,
+                                                             char* __restrict__ dst, int N, int K) {
     constexpr int ES = sizeof(T), EPP = 16 / ES;
     const size_t piece = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t n_pieces = (size_t)N * K / EPP;
     if (piece >= n_pieces) return;
     const int n = (int)(piece / (K / EPP));
     const int k = (int)(piece % (K / EPP)) * EPP;
-    const f32x4 v = *reinterpret_cast<const f32x4*>(src + (size_t)n * K + k);  // 16 bytes, any type
-    *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(n, k, K)) = v;
+    T v[EPP];
+    *reinterpret_cast<f32x4*>(v) = *reinterpret_cast<const f32x4*>(src + (size_t)n * K + k);  // 16 bytes, any type
+    if (gain) {
+#pragma unroll
+        for (int e = 0; e < EPP; ++e) v[e] = from_f32<T>(to_f32(v[e]) * to_f32(gain[k + e]));
+    }
+    *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(n, k, K)) = *reinterpret_cast<const f32x4*>(v);
 }
 
 // dst (fragment order, [M, K]) <- rows of a row-major source, row m taken from src row row_map[m] (or m)
@@ -596,16 +599,16 @@ hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, vo
     return hipGetLastError();
 }
 
-hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s) {
+hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s) {
     if (N % 16 != 0 || K % 64 != 0) return hipErrorInvalidValue;
     const size_t pieces = (size_t)N * K / (dt == kBF16 ? 8 : 4);
     dim3 grid((unsigned)((pieces + 255) / 256));
     if (dt == kBF16)
         hipLaunchKernelGGL(reorder_weight_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(src),
-                           static_cast<char*>(dst), N, K);
+                           static_cast<const bf16_t*>(gain), static_cast<char*>(dst), N, K);
     else
         hipLaunchKernelGGL(reorder_weight_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(src),
-                           static_cast<char*>(dst), N, K);
+                           static_cast<const float*>(gain), static_cast<char*>(dst), N, K);
     return hipGetLastError();
 }
 

@@ -12,11 +12,13 @@ constexpr int kPage = 16;  // tokens per self-attention KV page
 // ---------------------------------------------------------------- decode GEMM
 // C[M,N] = prologue(A)[M,K] . W[N,K]^T (+bias), then an epilogue.
 // PRO_LNS (bfloat16 mode): the LayerNorm is folded around the product instead of being applied to the operand.
-// Whoever writes the residual rows x (embedding, EPI_RESID_S) also writes their "shadow" (x - mu_hat) * g in the
+// Whoever writes the residual rows x (embedding, EPI_RESID_S) also writes their "shadow" x - mu_hat in the
 // storage type and fragment order (mu_hat: the row mean before the update, so the shadow has no large common
-// offset; g: gain of the LayerNorm that reads it) and per-row statistics of x, and then
-//   W . LN(x) + bias = rstd * (W . shadow - (mu - mu_hat) * c1) + c2,  c1 = W . g,  c2 = W . b + bias,
-// so the product streams half the bytes of the float32 rows and needs no pass over them first.
+// offset) and per-row statistics of x; the gain g of the LayerNorm is multiplied into the matrix once, when the
+// decoder is created (Wg = W . diag(g), rounded to the storage type), and then
+//   W . LN(x) + bias = rstd * (Wg . shadow - (mu - mu_hat) * c1) + c2,  c1 = Wg . 1,  c2 = W . b + bias,
+// so the product streams half the bytes of the float32 rows and needs no pass over them first, and one shadow
+// serves every product that reads the rows.
 enum GemmPro { PRO_LN = 0, PRO_T = 1, PRO_LNS = 2 };
 // EPI_RESID_S: EPI_RESID that also writes the shadow and the statistics of the updated rows.
 enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROSSKV = 4, EPI_RESID_S = 5 };
@@ -56,7 +58,6 @@ struct GemmArgs {
     float* mu_hat_out;       // PRO_LNS: [M] row means of A's rows, for the residual update that follows
     float2* stats_out;       // EPI_RESID_S: of the updated rows
     void* shadow_out;        // EPI_RESID_S: T [M,N] fragment order
-    const void* shadow_g;    // EPI_RESID_S: T [N]
     int stat_tiles, m_stride;
     int kv_fp8;              // EPI_QKV / EPI_CROSSKV: the caches hold 8-bit E4M3 codes instead of T
     int rms;                 // the normalisation is RMSNorm (no mean subtraction; ln_b may be null) instead of LayerNorm:
@@ -77,11 +78,13 @@ hipError_t launch_gemm_dma128(GemmEpi epi, const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s);
 // dst (fragment order [M,K]) <- rows of a row-major source; row m comes from src row row_map[m] (or m); K % 64 == 0
 hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, void* dst, int M, int K, hipStream_t s);
-// c1[n] = sum_k W[n,k] g[k], c2[n] = sum_k W[n,k] b[k] + bias[n] (float32 sums; W row-major [N,K], bias may be null)
+// c1[n] = sum_k T(W[n,k] g[k]) (the column-scaled matrix as it is stored), c2[n] = sum_k W[n,k] b[k] + bias[n]
+// (float32 sums; W row-major [N,K]; b and bias may be null)
 hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b, const void* bias, float* c1, float* c2,
                           int N, int K, hipStream_t s);
-// dst (fragment order) <- src (row-major [N,K]); N % 16 == 0, K % 64 == 0
-hipError_t launch_reorder_weight(Dtype dt, const void* src, void* dst, int N, int K, hipStream_t s);
+// dst (fragment order) <- src (row-major [N,K]), each column k multiplied by gain[k] if gain is given (T [K];
+// the product is rounded to T once); N % 16 == 0, K % 64 == 0
+hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s);
 
 // ---------------------------------------------------------------- decode attention
 struct AttnArgs {
@@ -125,8 +128,7 @@ struct StateArgs {
 // What the folded LayerNorm of the first layer needs beside the rows themselves (bfloat16 mode; see PRO_LNS).
 // shadow == null: not written.
 struct ShadowArgs {
-    void* shadow;       // T [B, d] fragment order: (x - row mean) * g
-    const void* g;      // T [d]: gain of the LayerNorm that reads the shadow
+    void* shadow;       // T [B, d] fragment order: x - row mean
     float2* stats;      // [d / 16][m_stride]: mean and sum of squared deviations of every 16-column tile
     float* mu_hat;      // [B] row means (the shadow's shift)
     int m_stride;

@@ -53,8 +53,7 @@ __global__ __launch_bounds__(256) void embed_kernel(float* __restrict__ x, const
     q += __shfl_xor(q, 1);
     q += __shfl_xor(q, 2);
     if (!live) return;
-    const f32x4 gv = load4(static_cast<const T*>(sh.g) + i);
-    store4(reinterpret_cast<T*>(static_cast<char*>(sh.shadow) + frag_elem_off<sizeof(T)>(b, i, d)), (o - mean) * gv);
+    store4(reinterpret_cast<T*>(static_cast<char*>(sh.shadow) + frag_elem_off<sizeof(T)>(b, i, d)), o - mean);
     if ((tid & 3) == 0) sh.stats[(size_t)(i >> 4) * sh.m_stride + b] = float2{tmean, q};
     if (tid == 0) sh.mu_hat[b] = mean;
 }
