@@ -59,14 +59,16 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Offsets (bytes) of everything carved from the caller's workspace.
 struct Layout {
-    size_t x, q, logits, attn_out, ffn_h, ln_h, x_shadow, ln_stats, mu_hat, ln_fold;
+    size_t x, q, q_aux, logits, attn_out, ffn_h, ln_h, x_shadow, ln_stats, mu_hat, ln_fold;
     size_t stats_elems;  // float2 per statistics buffer
+    size_t shadow_bytes; // bytes per shadow buffer
     size_t act_bytes;    // [0, act_bytes): the step's activations and attention partials (x ... counters)
     size_t seq_len, n_gen, finished, cur_tok, limit, limits_in, n_finished, step_tok;
     size_t prompt_buf, out_buf, page_table, enc_off, row_map, frame_map, turn_buf, items, part, counters;
     size_t v_seq_len, v_finished, v_cur_tok, v_page_table, v_items;  // state of a prompt-prefill pass's rows
     int act_rows;  // rows the activation buffers hold: max(max_batch, prefill_rows)
     size_t k_pool, v_pool, kc, vc, w_frag, enc_frag;
+    size_t w_merge, merge_vec;  // bfloat16 mode: the merged products' matrices and bias vectors (kernels.h)
     size_t total;
     int max_pages, n_pages, max_items;
     size_t pool_layer_elems, cross_layer_elems;
@@ -116,13 +118,15 @@ void make_layout(const aed_config* c, Layout* L) {
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L->x = take(Bp * d * 4);
     L->q = take(Ba * d * 4);
+    L->q_aux = take(c->dtype == 1 ? Ba * d * 4 : 0);  // merged products: the part of the cross-attention query that the QKV launch computes
     L->logits = take(B * (size_t)c->vocab * 4);
     L->attn_out = take(Bp * d * e);
     L->ffn_h = take(Bp * (size_t)c->d_ffn * e);
     L->ln_h = take(Bp * d * e);
     // bfloat16 mode: LayerNorm folded around the products (shadow of the residual rows, tile statistics in two
     // buffers that alternate from one residual update to the next, row shifts, folded gain/shift vectors)
-    L->x_shadow = take(Bp * d * e);
+    L->x_shadow = take(2 * Bp * d * e);  // two buffers, alternating like the statistics
+    L->shadow_bytes = Bp * d * e;
     L->stats_elems = (d / 16) * Bp;
     L->ln_stats = take(2 * L->stats_elems * 8);
     L->mu_hat = take(2 * Bp * 4);  // two buffers, alternating like the statistics
@@ -158,6 +162,9 @@ void make_layout(const aed_config* c, Layout* L) {
     L->vc = take(L->cross_layer_elems * c->n_layers * ekv);
     // every weight matrix once more, in MFMA fragment order
     L->w_frag = take(((size_t)c->n_layers * (8 * d * d + 2 * d * (size_t)c->d_ffn) + (size_t)c->vocab * d) * e);
+    // merged products (bfloat16 mode): per layer Wcq.g . Wo and the vector Wcq.g . bo
+    L->w_merge = take(c->dtype == 1 ? (size_t)c->n_layers * (d * d) * e : 0);
+    L->merge_vec = take(c->dtype == 1 ? (size_t)c->n_layers * d * 4 : 0);
     // the batch's encoder states in fragment order (A operand of the cross K/V GEMMs), whole 256-row tiles
     L->enc_frag = take(align_up((size_t)c->max_total_enc_frames, 256) * d * e);
     L->total = off;
@@ -197,6 +204,8 @@ struct aed_decoder {
     struct LnFold { const float *qkv_c1, *qkv_c2, *cq_c1, *cq_c2, *ff1_c1, *ff1_c2; };
     std::vector<LnFold> fold;               // bfloat16 mode: W . g and W . b + bias of every LayerNorm product
     const float *out_c1 = nullptr, *out_c2 = nullptr;
+    struct Merged { const void* w_p2; const float* cb_cq; };  // Wcq.g . Wo (fragment order), Wcq.g . bo
+    std::vector<Merged> mw;
     int x_par = 0;                          // which statistics buffer describes the current residual rows
     const void* fw_out = nullptr;
     hipStream_t stream;
@@ -312,18 +321,28 @@ float2* stats_buf(const aed_decoder* d, int par) {
 float* shift_buf(const aed_decoder* d, int par) {
     return d->act_at<float>(d->lay.mu_hat) + (size_t)par * (d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
 }
-void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float* c2) {
-    g.A = d->act + d->lay.x_shadow;
-    // rows of version v (parity p): statistics in buffer p; the shadow was shifted by the mean of version v-1,
-    // which that version's product left in shift buffer p^1; this product leaves the mean of version v in buffer p
+char* shadow_buf(const aed_decoder* d, int par) { return d->act + d->lay.x_shadow + (size_t)par * d->lay.shadow_bytes; }
+// Rows of version v (parity p = x_par): statistics in statistics buffer p, shadow in shadow buffer p.  The shift of a
+// shadow is one value per row and layer: every shadow written inside layer l (by its three residual updates) is
+// shifted by the mean the rows had when they entered the layer, which the layer's first product (QKV) leaves in
+// shift buffer l & 1; the rows entering layer l carry the shift of layer l - 1 (buffer (l & 1) ^ 1; the embedding
+// writes buffer 1 for layer 0).  first: this product is the one that reads the rows entering `layer` (QKV, or the
+// vocabulary product with layer = n_layers).
+void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float* c2, int layer, bool first) {
+    g.A = shadow_buf(d, d->x_par);
     g.stats_in = stats_buf(d, d->x_par);
-    g.mu_hat_in = shift_buf(d, d->x_par ^ 1);
-    g.mu_hat_out = shift_buf(d, d->x_par);
+    g.mu_hat_in = shift_buf(d, first ? (layer & 1) ^ 1 : layer & 1);
+    g.mu_hat_out = first && layer < d->cfg.n_layers ? shift_buf(d, layer & 1) : nullptr;
     g.ln_c1 = c1;
     g.ln_c2 = c2;
     g.stat_tiles = d->cfg.d_model / 16;
     g.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
 }
+
+// Small batches in bfloat16 mode: the cross-attention query product is split over the QKV launch and the launch of the
+// self-attention output projection (kernels.h, "merged products"): one launch fewer per layer.
+constexpr int kMergeMaxRows = 128;
+bool merged_products(const aed_decoder* d) { return folded_ln(d) && d->batch <= kMergeMaxRows; }
 
 hipError_t k_ln_qkv(aed_decoder* d, int l) {
     const aed_layer_weights& w = d->layers[l];
@@ -339,7 +358,13 @@ hipError_t k_ln_qkv(aed_decoder* d, int l) {
     g.seq_len = d->at<int>(d->lay.seq_len);
     g.finished = d->at<int>(d->lay.finished);
     if (folded_ln(d)) {
-        ln_consumer(d, g, d->fold[l].qkv_c1, d->fold[l].qkv_c2);
+        ln_consumer(d, g, d->fold[l].qkv_c1, d->fold[l].qkv_c2, l, true);
+        if (merged_products(d)) {  // the stored matrix is [Wqkv.g1 ; Wcq.g2]: the last d columns are P1 of the merged products
+            g.N = 4 * d->cfg.d_model;
+            g.n_raw = 3 * d->cfg.d_model;
+            g.out2 = d->act_at<float>(d->lay.q_aux);
+            g.raw_bias = d->mw[l].cb_cq;
+        }
         return launch_gemm(d->dt, PRO_LNS, EPI_QKV, g, d->stream);
     }
     return launch_gemm(d->dt, PRO_LN, EPI_QKV, g, d->stream);
@@ -382,14 +407,37 @@ hipError_t k_resid(aed_decoder* d, int l, const void* A, const void* W, const vo
     g.out = d->act_at<float>(d->lay.x);
     if (folded_ln(d)) {
         g.stats_out = stats_buf(d, d->x_par ^ 1);
-        g.mu_hat_in = shift_buf(d, d->x_par);  // mean of the rows before the update, left by the product that read them
-        g.shadow_out = d->act + d->lay.x_shadow;
+        g.mu_hat_in = shift_buf(d, l & 1);  // the mean of the rows that entered the layer
+        g.shadow_out = shadow_buf(d, d->x_par ^ 1);
         g.stat_tiles = d->cfg.d_model / 16;
         g.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
         d->x_par ^= 1;
         return launch_gemm(d->dt, PRO_T, EPI_RESID_S, g, d->stream);
     }
     return launch_gemm(d->dt, PRO_T, EPI_RESID, g, d->stream);
+}
+
+// x += Wo . o + bo and, in the same launch, P2 = (Wcq.g . Wo) . o -> q (finished by cross-attention)
+hipError_t k_self_out_crossq(aed_decoder* d, int l) {
+    const aed_layer_weights& w = d->layers[l];
+    const int dm = d->cfg.d_model;
+    GemmArgs a0 = gemm_base(d, l);
+    a0.A = d->act + d->lay.attn_out; a0.W = d->fw[l].w_o; a0.bias = w.b_o;
+    a0.N = dm; a0.K = dm;
+    a0.out = d->act_at<float>(d->lay.x);
+    a0.stats_out = stats_buf(d, d->x_par ^ 1);
+    a0.mu_hat_in = shift_buf(d, l & 1);
+    a0.shadow_out = shadow_buf(d, d->x_par ^ 1);
+    a0.stat_tiles = dm / 16;
+    a0.m_stride = (int)(d->lay.stats_elems / (size_t)(dm / 16));
+    GemmArgs a1 = gemm_base(d, l);
+    a1.A = d->act + d->lay.attn_out;
+    a1.W = d->mw[l].w_p2;
+    a1.N = dm; a1.K = dm;
+    a1.out = d->act_at<float>(d->lay.q);
+    a1.addend = d->act_at<float>(d->lay.q_aux);  // P1, left by the layer's QKV launch
+    d->x_par ^= 1;
+    return launch_gemm_pair(d->dt, a0, EPI_F32, a1, d->stream);
 }
 
 hipError_t k_ln_crossq(aed_decoder* d, int l) {
@@ -400,7 +448,7 @@ hipError_t k_ln_crossq(aed_decoder* d, int l) {
     g.N = d->cfg.d_model; g.K = d->cfg.d_model;
     g.out = d->act_at<float>(d->lay.q);
     if (folded_ln(d)) {
-        ln_consumer(d, g, d->fold[l].cq_c1, d->fold[l].cq_c2);
+        ln_consumer(d, g, d->fold[l].cq_c1, d->fold[l].cq_c2, l, false);
         return launch_gemm(d->dt, PRO_LNS, EPI_F32, g, d->stream);
     }
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
@@ -415,6 +463,16 @@ hipError_t k_cross_attn(aed_decoder* d, int l) {
     a.enc_off = d->at<int>(d->lay.enc_off);
     a.chunk = d->cross_chunk;
     a.t_cap = d->cfg.max_total_enc_frames;
+    if (merged_products(d)) {  // q holds the merged product: the kernel finishes the normalisation
+        a.q_stats = stats_buf(d, d->x_par);        // of the rows after the self-attention update
+        a.q_mu_hat = shift_buf(d, (l & 1) ^ 1);    // shift of the shadow of the rows that entered the layer
+        a.q_c1 = d->fold[l].cq_c1;
+        a.q_c2 = d->fold[l].cq_c2;
+        a.q_eps = d->cfg.ln_eps;
+        a.q_stat_tiles = d->cfg.d_model / 16;
+        a.q_m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
+        a.q_rms = d->cfg.norm_type == 1;
+    }
     return launch_attn_cross(d->dt, a, d->stream);
 }
 
@@ -426,7 +484,7 @@ hipError_t k_ln_ffn1(aed_decoder* d, int l) {
     g.N = d->cfg.d_ffn; g.K = d->cfg.d_model;
     g.out = d->act + d->lay.ffn_h;
     if (folded_ln(d)) {
-        ln_consumer(d, g, d->fold[l].ff1_c1, d->fold[l].ff1_c2);
+        ln_consumer(d, g, d->fold[l].ff1_c1, d->fold[l].ff1_c2, l, false);
         return launch_gemm(d->dt, PRO_LNS, EPI_RELU_T, g, d->stream);
     }
     return launch_gemm(d->dt, PRO_LN, EPI_RELU_T, g, d->stream);
@@ -439,7 +497,7 @@ hipError_t k_ln_vocab(aed_decoder* d) {
     g.N = d->cfg.vocab; g.K = d->cfg.d_model;
     g.out = d->act_at<float>(d->lay.logits);
     if (folded_ln(d)) {
-        ln_consumer(d, g, d->out_c1, d->out_c2);
+        ln_consumer(d, g, d->out_c1, d->out_c2, d->cfg.n_layers, true);
         return launch_gemm(d->dt, PRO_LNS, EPI_F32, g, d->stream);
     }
     return launch_gemm(d->dt, PRO_LN, EPI_F32, g, d->stream);
@@ -461,12 +519,21 @@ hipError_t k_cross_kv(aed_decoder* d, int l, long long rows, const int* frame_ma
     return launch_gemm(d->dt, PRO_T, EPI_CROSSKV, g, d->stream);  // LDS-tiled kernel from 512 rows (bf16)
 }
 
+// launches of a kernel class per layer in the current mode
+int class_launches(const aed_decoder* d, int cls) {
+    if (merged_products(d) && cls == AED_K_LN_CROSSQ) return 0;  // part of AED_K_SELF_OUT's launch
+    return 1;
+}
+
 hipError_t k_class(aed_decoder* d, int cls, int l) {
     const aed_layer_weights& w = d->layers[l];
+    if (class_launches(d, cls) == 0) return hipSuccess;
     switch (cls) {
         case AED_K_LN_QKV: return k_ln_qkv(d, l);
         case AED_K_SELF_ATTN: return k_self_attn(d, l);
-        case AED_K_SELF_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model);
+        case AED_K_SELF_OUT:
+            if (merged_products(d)) return k_self_out_crossq(d, l);
+            return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_o, w.b_o, d->cfg.d_model);
         case AED_K_LN_CROSSQ: return k_ln_crossq(d, l);
         case AED_K_CROSS_ATTN: return k_cross_attn(d, l);
         case AED_K_CROSS_OUT: return k_resid(d, l, d->act + d->lay.attn_out, d->fw[l].w_co, w.b_co, d->cfg.d_model);
@@ -485,9 +552,9 @@ hipError_t enqueue_step(aed_decoder* d, const StateArgs& st, int greedy, int* st
     memset(&sa, 0, sizeof sa);
     if (folded_ln(d)) {
         d->x_par = 0;
-        sa.shadow = d->act + d->lay.x_shadow;
+        sa.shadow = shadow_buf(d, 0);
         sa.stats = stats_buf(d, 0);
-        sa.mu_hat = shift_buf(d, 1);  // read as the shift of version 0 by the first product
+        sa.mu_hat = shift_buf(d, 1);  // read as the shift of the rows entering layer 0
         sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
         sa.rms = d->cfg.norm_type == 1;
     }
@@ -669,7 +736,7 @@ aed_status prefill_pass(aed_decoder* d, const std::vector<int>& prompt_host, int
         memset(&sa, 0, sizeof sa);
         if (folded_ln(d)) {
             d->x_par = 0;
-            sa.shadow = d->act + d->lay.x_shadow;
+            sa.shadow = shadow_buf(d, 0);
                 sa.stats = stats_buf(d, 0);
             sa.mu_hat = shift_buf(d, 1);
             sa.m_stride = (int)(d->lay.stats_elems / (size_t)(d->cfg.d_model / 16));
@@ -794,8 +861,8 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
             const aed_layer_weights& x = d->layers[l];
             aed_decoder::FragWeights& f = d->fw[l];
             f.w_qkv = put(x.w_qkv, 3 * dm, dm, x.ln1_g);
+            f.w_cq = put(x.w_cq, dm, dm, x.ln2_g);  // directly behind w_qkv: together the [4 d, d] matrix of the merged QKV launch
             f.w_o = put(x.w_o, dm, dm);
-            f.w_cq = put(x.w_cq, dm, dm, x.ln2_g);
             f.w_ckv = put(x.w_ckv, 2 * dm, dm);
             f.w_co = put(x.w_co, dm, dm);
             f.w_ff1 = put(x.w_ff1, F, dm, x.ln3_g);
@@ -824,6 +891,23 @@ aed_status aed_decoder_create(const aed_config* cfg, const aed_weights* weights,
         }
         fold(d->w.w_out, d->w.lnf_g, d->w.lnf_b, d->w.b_out, cfg->vocab, &d->out_c1, &d->out_c2);
         if (e != hipSuccess) return cleanup(e, "folding LayerNorm gain and shift into the products");
+    }
+    if (folded_ln(d)) {  // merged products: Wcq.g . Wo and Wcq.g . bo per layer
+        const int dm = cfg->d_model;
+        char* p = d->ws + L.w_merge;
+        float* v = reinterpret_cast<float*>(d->ws + L.merge_vec);
+        e = hipSuccess;
+        d->mw.resize(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
+            const aed_layer_weights& x = d->layers[l];
+            e = launch_weight_product(d->dt, x.w_cq, x.ln2_g, x.w_o, p, dm, dm, dm, 0, dm, d->stream);
+            if (e == hipSuccess) e = launch_fold_vec(d->dt, x.w_cq, x.ln2_g, x.b_o, v, dm, dm, d->stream);
+            d->mw[l].w_p2 = p;
+            d->mw[l].cb_cq = v;
+            p += (size_t)dm * dm * d->esz;
+            v += dm;
+        }
+        if (e != hipSuccess) return cleanup(e, "forming the merged products' matrices");
     }
     if ((e = hipStreamSynchronize(d->stream)) != hipSuccess) return cleanup(e, "hipStreamSynchronize");
     *out = d;
@@ -1321,7 +1405,7 @@ aed_status aed_time_kernels(aed_decoder* d, int32_t cls, int32_t reps, float* ms
     HIP_TRY(d, hipEventRecord(d->t0, d->stream));
     for (int r = 0; r < reps; ++r) {
         if (cls == AED_K_LN_VOCAB) { HIP_TRY(d, k_ln_vocab(d)); ++n; continue; }
-        for (int l = 0; l < d->cfg.n_layers; ++l) { HIP_TRY(d, k_class(d, cls, l)); ++n; }
+        for (int l = 0; l < d->cfg.n_layers; ++l) { HIP_TRY(d, k_class(d, cls, l)); n += class_launches(d, cls); }
     }
     HIP_TRY(d, hipEventRecord(d->t1, d->stream));
     HIP_TRY(d, hipEventSynchronize(d->t1));
@@ -1350,9 +1434,26 @@ aed_status aed_kernel_work(aed_decoder* d, int32_t cls, double* bytes, double* f
         *flops = 2 * M * N * K;
     };
     switch (cls) {
-        case AED_K_LN_QKV: gemm(B, 3 * dm, dm, 4, 0, true, false); *bytes += B * dm * 4 + 2 * B * dm * ekv; break;
-        case AED_K_SELF_OUT: case AED_K_CROSS_OUT: gemm(B, dm, dm, e, 8, false, true); break;
-        case AED_K_LN_CROSSQ: gemm(B, dm, dm, 4, 4, true, false); break;
+        case AED_K_LN_QKV:
+            gemm(B, 3 * dm, dm, 4, 0, true, false);
+            *bytes += B * dm * 4 + 2 * B * dm * ekv;
+            if (merged_products(d)) {  // the part of the cross-attention query product that reads the same rows rides along
+                *bytes += dm * dm * e + B * dm * 4;
+                *flops += 2 * B * dm * dm;
+            }
+            break;
+        case AED_K_SELF_OUT:
+            gemm(B, dm, dm, e, 8, false, true);
+            if (merged_products(d)) {  // the part of the cross-attention query product that reads o rides along
+                *bytes += dm * dm * e + B * dm * 4;
+                *flops += 2 * B * dm * dm;
+            }
+            break;
+        case AED_K_CROSS_OUT: gemm(B, dm, dm, e, 8, false, true); break;
+        case AED_K_LN_CROSSQ:
+            if (merged_products(d)) { *bytes = 0; *flops = 0; break; }
+            gemm(B, dm, dm, 4, 4, true, false);
+            break;
         case AED_K_LN_FFN1: gemm(B, F, dm, 4, e, true, false); break;
         case AED_K_FFN2: gemm(B, dm, F, e, 8, false, true); break;
         case AED_K_LN_VOCAB: gemm(B, V, dm, 4, 4, true, false); break;

@@ -104,8 +104,10 @@ template <int LPK> __device__ __forceinline__ float keys_max(float v) {
 
 // T: type of the output rows (and of the caches unless KV says otherwise); KV: what the caches hold;
 // LPK: lanes that share a key row.
+// (bfloat16 and 8-bit caches: at least four wavefronts per SIMD, i.e. at most 128 registers, so that two workgroups of
+// eight wavefronts share a CU -- with one, half as many bytes are in flight and the launch takes a quarter longer)
 template <typename T, typename KV, int LPK, int DH, bool SELF, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * NW, sizeof(KV) <= 2 ? 4 : 1) void attn_decode_kernel(AttnArgs a) {
     constexpr int EPL = DH / LPK;   // head_dim elements per lane
     constexpr int KPI = 64 / LPK;   // keys per load instruction
     constexpr int NI = 16 / KPI;    // load instructions per 16-key block
@@ -150,6 +152,29 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
     const int n_blocks = (n + 15) >> 4;
     const int* __restrict__ pages = SELF ? a.page_table + (size_t)b * a.max_pages + (start >> 4) : nullptr;
 
+    // the query row slice and, behind merged products, what finishes it: requested here, before the first key
+    // blocks, and used after them, so that the keys and values do not wait for this round trip
+    float q[EPL];
+    float qc1[EPL], qc2[EPL];
+    float2 q_st = float2{0.f, 0.f};
+    float q_muh = 0.f;
+    bool q_fix = false;
+    {
+        const size_t qo = (size_t)b * H * DH + h * DH + r * EPL;
+        load_f32<EPL>(a.q + qo, q);
+        if constexpr (!SELF) {
+            q_fix = a.q_stats != nullptr;
+            if (q_fix) {
+                const int n0 = h * DH + r * EPL;
+                load_f32<EPL>(a.q_c1 + n0, qc1);
+                load_f32<EPL>(a.q_c2 + n0, qc2);
+                // the row's tile statistics (at most 64: one lane each) are 64 separate lines: only the first wavefront
+                // gathers them and hands the two numbers that come out to the others through LDS
+                if (wave == 0 && lane < a.q_stat_tiles) q_st = a.q_stats[(size_t)lane * a.q_m_stride + b];
+                q_muh = a.q_mu_hat[b];
+            }
+        }
+    }
     typedef RawRow<KV, EPL> Raw;
     // element offset of this lane's slice of key (KPI i + g) of block kb (clamped to the valid keys)
     auto fetch = [&](int kb, Raw* kf, Raw* vf) {
@@ -166,14 +191,31 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
             vf[i] = load_raw<EPL>(Vb + off);
         }
     };
-
-    float q[EPL];
-    {
-        const float* qp = a.q + (size_t)b * H * DH + h * DH + r * EPL;
-        load_f32<EPL>(qp, q);
+    // two blocks in flight per wavefront: fetch block i+1 while block i is consumed
+    Raw k0[NI], v0[NI], k1[NI], v1[NI];
+    int kb = wave;
+    if (kb < n_blocks) fetch(kb, k0, v0);
+    if constexpr (!SELF) {
+        if (fin) return;
+        if (q_fix) {  // q = rstd' (P - (mu' - mu_hat) c1) + c2 with this row's statistics
+            __shared__ float sm_fix[2];
+            if (wave == 0) {
+                const int tiles = a.q_stat_tiles;
+                float mu = wave_sum(q_st.x) / (float)tiles;
+                const float dev = lane < tiles ? (q_st.x - mu) * (q_st.x - mu) : 0.f;
+                const float m2 = wave_sum(q_st.y) + 16.f * wave_sum(dev);
+                const float r0 = fold_norm(a.q_rms, 16.f * (float)tiles, a.q_eps, m2, mu);
+                if (lane == 0) { sm_fix[0] = r0; sm_fix[1] = mu - q_muh; }
+            }
+            // LDS only: the key / value loads in flight are not waited for here
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const float rstd = sm_fix[0], shift = sm_fix[1];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) q[e] *= a.scale_log2e;
+            for (int e = 0; e < EPL; ++e) q[e] = rstd * (q[e] - shift * qc1[e]) + qc2[e];
+        }
     }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) q[e] *= a.scale_log2e;
 
     float m_run = -INFINITY, l_run = 0.f;
     float acc[EPL];
@@ -211,13 +253,6 @@ __global__ __launch_bounds__(64 * NW) void attn_decode_kernel(AttnArgs a) {
         m_run = m_new;
     };
 
-    // two blocks in flight per wavefront: fetch block i+1 while block i is consumed
-    Raw k0[NI], v0[NI], k1[NI], v1[NI];
-    int kb = wave;
-    if (kb < n_blocks) fetch(kb, k0, v0);
-    if constexpr (!SELF) {
-        if (fin) return;
-    }
     while (kb < n_blocks) {
         if (kb + NW < n_blocks) fetch(kb + NW, k1, v1);
         consume(kb, k0, v0);

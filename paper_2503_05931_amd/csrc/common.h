@@ -108,4 +108,24 @@ __device__ __forceinline__ float rows4_max(float v) {
     return v;
 }
 
+// Folded normalisation (kernels.h, PRO_LNS): from a row's mean mu and its sum of squared deviations m2 over K
+// elements, the factor the product is scaled with and the mean that counts.  LayerNorm: 1 / sqrt(m2 / K + eps) and mu.
+// RMSNorm: the mean is not subtracted, so the factor is 1 / sqrt(sum of squares / K + eps) with
+// sum of squares = m2 + K mu^2, and the row counts as having mean 0 (its shadow was written with shift 0).
+__device__ __forceinline__ float fold_norm(int rms, float K, float eps, float m2, float& mu) {
+    if (rms) {
+        const float r = 1.0f / sqrtf((m2 + K * mu * mu) / K + eps);
+        mu = 0.f;
+        return r;
+    }
+    return 1.0f / sqrtf(m2 / K + eps);
+}
+
+// sum over the 64 lanes of a wavefront; every lane gets the total
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
 }  // namespace aed

@@ -93,19 +93,6 @@ __device__ __forceinline__ void mma(f32x4& acc, const Frag16<float>& w, const Fr
     for (int i = 0; i < 16; ++i) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w.v[i], a.v[i], acc, 0, 0, 0);
 }
 
-// Folded normalisation (kernels.h, PRO_LNS): from a row's mean mu and its sum of squared deviations m2 over K
-// elements, the factor the product is scaled with and the mean that counts.  LayerNorm: 1 / sqrt(m2 / K + eps) and mu.
-// RMSNorm: the mean is not subtracted, so the factor is 1 / sqrt(sum of squares / K + eps) with
-// sum of squares = m2 + K mu^2, and the row counts as having mean 0 (its shadow was written with shift 0).
-__device__ __forceinline__ float fold_norm(int rms, float K, float eps, float m2, float& mu) {
-    if (rms) {
-        const float r = 1.0f / sqrtf((m2 + K * mu * mu) / K + eps);
-        mu = 0.f;
-        return r;
-    }
-    return 1.0f / sqrtf(m2 / K + eps);
-}
-
 // Four consecutive cache elements as 8-bit E4M3 codes (OCP 8-bit floating point: bias 7, no infinities, largest
 // magnitude 448): round to nearest even, done by the conversion instruction; saturation is done here.
 __device__ __forceinline__ void store4_fp8(unsigned char* p, f32x4 s) {

@@ -34,14 +34,15 @@ namespace aed {
 constexpr int kMaxLnBlocks = 4;  // PRO_LN: K <= 4 waves * 4 blocks * 64 = 1024
 constexpr int kMaxStatTilesPerGroup = 16;  // folded LayerNorm: d_model <= 1024 = 4 groups * 16 tiles * 16 columns
 
+// One output tile (column tile bx, row tile by) of the product described by a.
 // WNT: W is loaded with the non-temporal hint (GemmArgs::w_nt)
 template <typename T, int PRO, int EPI, int MT, int NT, bool WNT>
-__global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
+__device__ __forceinline__ void gemm_decode_body(const GemmArgs& a, const int bx, const int by) {
     constexpr int BM = 16 * MT, BN = 16 * NT;
     constexpr int EP = (MT * NT * 64 + 255) / 256;  // output 4-vectors per thread in the epilogue
     constexpr int ES = sizeof(T);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, g = lane >> 4;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int m0 = by * BM, n0 = bx * BN;
     const int K = a.K, M = a.M;
     const int nblk = K >> 8;  // 64-wide k blocks per wavefront
     const char* __restrict__ W = static_cast<const char*>(a.W);
@@ -78,8 +79,9 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         const bool live = idx < MT * NT * 64 && m < M;
         const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
         if constexpr (LNS) {
-            e_bias[j] = live ? *reinterpret_cast<const f32x4*>(a.ln_c2 + n) : zero;
-            e_aux[j] = live ? *reinterpret_cast<const f32x4*>(a.ln_c1 + n) : zero;
+            const bool raw = a.n_raw > 0 && n >= a.n_raw;  // columns from n_raw on are not normalised here
+            e_bias[j] = !live ? zero : *reinterpret_cast<const f32x4*>(raw ? a.raw_bias + (n - a.n_raw) : a.ln_c2 + n);
+            e_aux[j] = live && !raw ? *reinterpret_cast<const f32x4*>(a.ln_c1 + n) : zero;
         } else {
             e_bias[j] = (bias && live) ? load4(bias + n) : zero;
         }
@@ -87,6 +89,8 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
         if constexpr (RES)
             e_res[j] = live ? *reinterpret_cast<const f32x4*>(static_cast<const char*>(a.out) + frag_elem_off<4>(m, n, a.N))
                             : zero;
+        if constexpr (EPI == EPI_F32 && !LNS)  // optional addend, float [M,N] row-major like the output
+            e_res[j] = (live && a.addend) ? *reinterpret_cast<const f32x4*>(a.addend + (size_t)m * a.N + n) : zero;
     }
     // EPI_QKV: where this thread's key / value columns go in the paged cache (element index, -1: nowhere).  The
     // sequence's state and its page-table entry are two dependent loads; fetched here, they are off the critical
@@ -100,7 +104,7 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             const int m = m0 + (t / NT) * 16 + (l & 15);
             const int n = n0 + (t % NT) * 16 + (l >> 4) * 4;
             e_kv[j] = -1;
-            if (idx < MT * NT * 64 && m < M && n >= a.d_model && !a.finished[m]) {
+            if (idx < MT * NT * 64 && m < M && n >= a.d_model && n < 3 * a.d_model && !a.finished[m]) {
                 const int c = n - (n >= 2 * a.d_model ? 2 * a.d_model : a.d_model);
                 const int h = c / a.head_dim, e = c % a.head_dim;
                 const int pos = a.seq_len[m];
@@ -306,10 +310,16 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             float mu, m2;
             row_stats(mt * 16 + (l & 15), mu, m2);
             const float rstd = fold_norm(a.rms, (float)K, a.ln_eps, m2, mu), shift = mu - e_mu[j];
+            if (a.n_raw > 0 && n >= a.n_raw) {
+                // a product that belongs to a later normalisation of these rows (kernels.h, "merged products"):
+                // the bare sums (plus raw_bias) go to out2, whoever reads them finishes them
+                store4(a.out2 + (size_t)m * (a.N - a.n_raw) + (n - a.n_raw), s + e_bias[j]);
+                continue;
+            }
             s = (s - shift * e_aux[j]) * rstd + e_bias[j];
             if constexpr (EPI == EPI_QKV) store_qkv(m, n, s, e_kv[j]);
             else gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
-            if (n == 0) a.mu_hat_out[m] = mu;  // the next residual update shifts its shadow by this
+            if (n == 0 && a.mu_hat_out) a.mu_hat_out[m] = mu;  // the layer's residual updates shift their shadows by this
         } else if constexpr (RS) {
             const float mu_old = e_mu[j];
             const f32x4 x = e_res[j] + s + e_bias[j];
@@ -329,9 +339,30 @@ __global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
             }
         } else {
             s += e_bias[j];
+            if constexpr (EPI == EPI_F32) s += e_res[j];
             if constexpr (EPI == EPI_QKV) store_qkv(m, n, s, e_kv[j]);
             else gemm_epilogue<T, EPI>(a, m, n, s, e_res[j]);
         }
+    }
+}
+
+template <typename T, int PRO, int EPI, int MT, int NT, bool WNT>
+__global__ __launch_bounds__(256) void gemm_decode_kernel(GemmArgs a) {
+    gemm_decode_body<T, PRO, EPI, MT, NT, WNT>(a, blockIdx.x, blockIdx.y);
+}
+
+// Two products of the same operand in one launch: the first n0 workgroups are the tiles of a0 (a residual update,
+// EPI_RESID_S), the others the tiles of a1 (kernels.h, "merged products").  Neither reads what the other writes.
+template <typename T, int MT0, int NT0, int EPI1, int MT1, int NT1, bool WNT>
+__global__ __launch_bounds__(256) void gemm_decode_pair_kernel(GemmArgs a0, GemmArgs a1, int n0) {
+    int b = blockIdx.x;
+    if (b < n0) {
+        const int nx = a0.N / (16 * NT0);
+        gemm_decode_body<T, PRO_T, EPI_RESID_S, MT0, NT0, WNT>(a0, b % nx, b / nx);
+    } else {
+        b -= n0;
+        const int nx = a1.N / (16 * NT1);
+        gemm_decode_body<T, PRO_T, EPI1, MT1, NT1, WNT>(a1, b % nx, b / nx);
     }
 }
 
@@ -413,8 +444,8 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
 // Tile choice by a traffic model: each workgroup pulls (BM * bytes(A) + BN * bytes(W)) * K
 // through its CU and the launch's workgroups are spread over the 256 CUs; pick the
 // candidate with the least bytes per CU, then the fewest workgroups.
-template <typename T, int PRO, int EPI>
-static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
+template <typename T, int PRO>
+static int choose_tile(const GemmArgs& a) {
     struct Cand { int mt, nt; };
     static const Cand cands[] = {{1, 1}, {2, 2}, {2, 4}, {4, 2}, {4, 4}};
     const double a_bytes = PRO == PRO_LN ? 4.0 : sizeof(T), w_bytes = sizeof(T);
@@ -436,6 +467,12 @@ static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
         const double cost = rounds * (bm * a_bytes + bn * w_bytes) * (c == 4 ? 1.6 : 1.0);
         if (cost < best_cost || (cost == best_cost && wgs < best_wgs)) { best = c; best_cost = cost; best_wgs = wgs; }
     }
+    return best;
+}
+
+template <typename T, int PRO, int EPI>
+static hipError_t launch_tiles(const GemmArgs& a, hipStream_t s) {
+    const int best = choose_tile<T, PRO>(a);
     if (best == 0) return launch_one<T, PRO, EPI, 1, 1>(a, s);
     if (best == 1) return launch_one<T, PRO, EPI, 2, 2>(a, s);
     if constexpr (PRO != PRO_LN) {
@@ -484,7 +521,7 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
     }
     if constexpr (sizeof(T) == 2) {
         if (pro == PRO_LNS) {
-            if (!a.stats_in || !a.mu_hat_in || !a.mu_hat_out || !a.ln_c1 || !a.ln_c2 || a.stat_tiles < 4 || a.stat_tiles % 4 != 0 ||
+            if (!a.stats_in || !a.mu_hat_in || !a.ln_c1 || !a.ln_c2 || a.stat_tiles < 4 || a.stat_tiles % 4 != 0 ||
                 a.stat_tiles > 4 * kMaxStatTilesPerGroup)
                 return hipErrorInvalidValue;
             if (use_tiled<T>(a)) return launch_gemm_tiled(epi, a, s);
@@ -507,6 +544,37 @@ static hipError_t launch_typed(GemmPro pro, GemmEpi epi, const GemmArgs& a0, hip
     if (pro == PRO_T && use_tiled<T>(a)) return launch_gemm_tiled(epi, a, s);
     if (pro == PRO_T && epi == EPI_RESID) return launch_tiles<T, PRO_T, EPI_RESID>(a, s);
     if (pro == PRO_T && epi == EPI_CROSSKV) return launch_tiles<T, PRO_T, EPI_CROSSKV>(a, s);
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------- two products in one launch
+template <typename T, int MT0, int NT0, int EPI1, int MT1, int NT1>
+static hipError_t launch_pair_one(const GemmArgs& a0, const GemmArgs& a1, hipStream_t s) {
+    const int n0 = (a0.N / (16 * NT0)) * ((a0.M + 16 * MT0 - 1) / (16 * MT0));
+    const int n1 = (a1.N / (16 * NT1)) * ((a1.M + 16 * MT1 - 1) / (16 * MT1));
+    if (a0.w_nt && a0.M <= kWntMaxM)
+        hipLaunchKernelGGL((gemm_decode_pair_kernel<T, MT0, NT0, EPI1, MT1, NT1, true>), dim3(n0 + n1), dim3(256), 0, s, a0, a1, n0);
+    else
+        hipLaunchKernelGGL((gemm_decode_pair_kernel<T, MT0, NT0, EPI1, MT1, NT1, false>), dim3(n0 + n1), dim3(256), 0, s, a0, a1, n0);
+    return hipGetLastError();
+}
+template <typename T, int EPI1>
+static hipError_t launch_pair_epi(const GemmArgs& a0, const GemmArgs& a1, hipStream_t s) {
+    // 16 x 16 or 32 x 32 tiles for each of the two (the batches this is used for have at most 128 rows)
+    const int t0 = choose_tile<T, PRO_T>(a0) > 0, t1 = choose_tile<T, PRO_T>(a1) > 0;
+    if (a0.N % 32 != 0 || a1.N % 32 != 0) return hipErrorInvalidValue;
+    if (!t0 && !t1) return launch_pair_one<T, 1, 1, EPI1, 1, 1>(a0, a1, s);
+    if (!t0 && t1) return launch_pair_one<T, 1, 1, EPI1, 2, 2>(a0, a1, s);
+    if (t0 && !t1) return launch_pair_one<T, 2, 2, EPI1, 1, 1>(a0, a1, s);
+    return launch_pair_one<T, 2, 2, EPI1, 2, 2>(a0, a1, s);
+}
+
+hipError_t launch_gemm_pair(Dtype dt, const GemmArgs& a0, GemmEpi epi1, const GemmArgs& a1, hipStream_t s) {
+    if (dt != kBF16 || a0.M < 1 || a0.M != a1.M || a0.M > 128 || a0.K % 256 != 0 || a1.K % 256 != 0) return hipErrorInvalidValue;
+    if (!a0.stats_out || !a0.mu_hat_in || !a0.shadow_out || a0.stat_tiles < 4 || a0.stat_tiles % 4 != 0 ||
+        a0.stat_tiles * 16 != a0.N || a0.stat_tiles > 4 * kMaxStatTilesPerGroup)
+        return hipErrorInvalidValue;
+    if (epi1 == EPI_F32) return launch_pair_epi<bf16_t, EPI_F32>(a0, a1, s);
     return hipErrorInvalidValue;
 }
 
@@ -559,7 +627,7 @@ hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b,
 // dst (fragment order) <- src (row-major [N, K]), columns scaled by gain (may be null); one thread per 16-byte piece.
 template <typename T>
 __global__ __launch_bounds__(256) void reorder_weight_kernel(const T* __restrict__ src, const T* __restrict__ gain,
-                                                             char* __restrict__ dst, int N, int K) {
+                                                             char* __restrict__ dst, int N, int K, int dst_k0, int dst_K) {
     constexpr int ES = sizeof(T), EPP = 16 / ES;
     const size_t piece = (size_t)blockIdx.x * 256 + threadIdx.x;
     const size_t n_pieces = (size_t)N * K / EPP;
@@ -572,7 +640,83 @@ __global__ __launch_bounds__(256) void reorder_weight_kernel(const T* __restrict
 #pragma unroll
         for (int e = 0; e < EPP; ++e) v[e] = from_f32<T>(to_f32(v[e]) * to_f32(gain[k + e]));
     }
-    *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(n, k, K)) = *reinterpret_cast<const f32x4*>(v);
+    *reinterpret_cast<f32x4*>(dst + frag_elem_off<ES>(n, dst_k0 + k, dst_K)) = *reinterpret_cast<const f32x4*>(v);
+}
+
+// Product of two weight matrices for a merged product (kernels.h): P[n, k] = sum_j T(W1[n, j] g[j]) W2[j, k], float32 sums
+// of the stored (rounded) factors, rounded to T once and written in fragment order into columns dst_k0 .. dst_k0 + K
+// of a matrix with dst_K columns.  W1 [N, J], W2 [J, K] row-major; g may be null.  One 64 x 64 output tile per
+// workgroup, 4 x 4 outputs per thread, 16-deep slices through LDS.  Runs once, when the decoder is created.
+template <typename T>
+__global__ __launch_bounds__(256) void weight_product_kernel(const T* __restrict__ W1, const T* __restrict__ g,
+                                                             const T* __restrict__ W2, char* __restrict__ dst, int N, int J,
+                                                             int K, int dst_k0, int dst_K) {
+    __shared__ float sa[16][64 + 4], sb[16][64 + 4];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int n0 = blockIdx.y * 64, k0 = blockIdx.x * 64;
+    float acc[4][4] = {};
+    for (int j0 = 0; j0 < J; j0 += 16) {
+        for (int i = tid; i < 64 * 16; i += 256) {
+            const int n = i >> 4, j = i & 15;  // W1 tile: 64 rows x 16 j, read along j
+            float w = to_f32(W1[(size_t)(n0 + n) * J + j0 + j]);
+            if (g) w = to_f32(from_f32<T>(w * to_f32(g[j0 + j])));
+            sa[j][n] = w;
+            const int jj = i >> 6, k = i & 63;  // W2 tile: 16 j x 64 columns, read along k
+            sb[jj][k] = to_f32(W2[(size_t)(j0 + jj) * K + k0 + k]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            float av[4], bv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { av[u] = sa[j][ty * 4 + u]; bv[u] = sb[j][tx * 4 + u]; }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] = fmaf(av[u], bv[v], acc[u][v]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int n = n0 + ty * 4 + u, k = k0 + tx * 4;
+        store4(reinterpret_cast<T*>(dst + frag_elem_off<sizeof(T)>(n, dst_k0 + k, dst_K)),
+               f32x4{acc[u][0], acc[u][1], acc[u][2], acc[u][3]});
+    }
+}
+
+hipError_t launch_weight_product(Dtype dt, const void* W1, const void* g, const void* W2, void* dst, int N, int J, int K,
+                                 int dst_k0, int dst_K, hipStream_t s) {
+    if (dt != kBF16 || N % 64 != 0 || K % 64 != 0 || J % 16 != 0 || dst_k0 % 64 != 0 || dst_K % 64 != 0 || dst_k0 + K > dst_K)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(weight_product_kernel<bf16_t>, dim3(K / 64, N / 64), dim3(256), 0, s, static_cast<const bf16_t*>(W1),
+                       static_cast<const bf16_t*>(g), static_cast<const bf16_t*>(W2), static_cast<char*>(dst), N, J, K, dst_k0, dst_K);
+    return hipGetLastError();
+}
+
+// out[n] = sum_j T(W[n, j] g[j]) v[j] (float32; v null: zeros).  One wavefront per n.
+template <typename T>
+__global__ __launch_bounds__(256) void fold_vec_kernel(const T* __restrict__ W, const T* __restrict__ g, const T* __restrict__ v,
+                                                       float* __restrict__ out, int N, int J) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    float sum = 0.f;
+    if (v)
+        for (int j = lane; j < J; j += 64) {
+            float w = to_f32(W[(size_t)n * J + j]);
+            if (g) w = to_f32(from_f32<T>(w * to_f32(g[j])));
+            sum += w * to_f32(v[j]);
+        }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) out[n] = sum;
+}
+
+hipError_t launch_fold_vec(Dtype dt, const void* W, const void* g, const void* v, float* out, int N, int J, hipStream_t s) {
+    if (dt != kBF16) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fold_vec_kernel<bf16_t>, dim3((N + 3) / 4), dim3(256), 0, s, static_cast<const bf16_t*>(W),
+                       static_cast<const bf16_t*>(g), static_cast<const bf16_t*>(v), out, N, J);
+    return hipGetLastError();
 }
 
 // dst (fragment order, [M, K]) <- rows of a row-major source, row m taken from src row row_map[m] (or m)
@@ -599,16 +743,18 @@ hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, vo
     return hipGetLastError();
 }
 
-hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s) {
-    if (N % 16 != 0 || K % 64 != 0) return hipErrorInvalidValue;
+hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s,
+                                 int dst_k0, int dst_K) {
+    if (dst_K <= 0) dst_K = K;
+    if (N % 16 != 0 || K % 64 != 0 || dst_k0 % 64 != 0 || dst_K % 64 != 0 || dst_k0 + K > dst_K) return hipErrorInvalidValue;
     const size_t pieces = (size_t)N * K / (dt == kBF16 ? 8 : 4);
     dim3 grid((unsigned)((pieces + 255) / 256));
     if (dt == kBF16)
         hipLaunchKernelGGL(reorder_weight_kernel<bf16_t>, grid, dim3(256), 0, s, static_cast<const bf16_t*>(src),
-                           static_cast<const bf16_t*>(gain), static_cast<char*>(dst), N, K);
+                           static_cast<const bf16_t*>(gain), static_cast<char*>(dst), N, K, dst_k0, dst_K);
     else
         hipLaunchKernelGGL(reorder_weight_kernel<float>, grid, dim3(256), 0, s, static_cast<const float*>(src),
-                           static_cast<const float*>(gain), static_cast<char*>(dst), N, K);
+                           static_cast<const float*>(gain), static_cast<char*>(dst), N, K, dst_k0, dst_K);
     return hipGetLastError();
 }
 

@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
                 const float m2 = row_stat[1][0][rl] + row_stat[1][1][rl] + stat_n * (d0 * d0 + d1 * d1);
                 rstd[mt] = fold_norm(a.rms, (float)K, a.ln_eps, m2, mu);
                 shift[mt] = m < a.M ? mu - a.mu_hat_in[m] : 0.f;
-                if (tn == 0 && wn == 0 && hh == 0 && m < a.M) a.mu_hat_out[m] = mu;  // for the next residual update
+                if (tn == 0 && wn == 0 && hh == 0 && m < a.M && a.mu_hat_out) a.mu_hat_out[m] = mu;  // for the residual updates
             }
         }
         const T* __restrict__ bias = static_cast<const T*>(a.bias);
@@ -265,7 +265,7 @@ static hipError_t launch_dma128_one(const GemmArgs& a, hipStream_t s) {
 hipError_t launch_gemm_dma128(GemmEpi epi, const GemmArgs& a, hipStream_t s) {
     if (a.M < 1 || a.N % kBN != 0 || a.K % 64 != 0 || a.K < 512) return hipErrorInvalidValue;
     if (a.ln_c1) {
-        if (!a.ln_c2 || !a.stats_in || !a.mu_hat_in || !a.mu_hat_out || a.stat_tiles < 2 || a.stat_tiles % 2 != 0 ||
+        if (!a.ln_c2 || !a.stats_in || !a.mu_hat_in || a.stat_tiles < 2 || a.stat_tiles % 2 != 0 ||
             a.stat_tiles > 64)
             return hipErrorInvalidValue;
         switch (epi) {

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmArgs a) {
             const float m2 = row_stat[1][0][rl] + row_stat[1][1][rl] + stat_n * (d0 * d0 + d1 * d1);
             rstd[i] = fold_norm(a.rms, (float)K, a.ln_eps, m2, mu);
             shift[i] = m0 + rl < a.M ? mu - a.mu_hat_in[m0 + rl] : 0.f;
-            if (n0 == 0 && wn == 0 && g == 0 && m0 + rl < a.M) a.mu_hat_out[m0 + rl] = mu;  // for the next residual update
+            if (n0 == 0 && wn == 0 && g == 0 && m0 + rl < a.M && a.mu_hat_out) a.mu_hat_out[m0 + rl] = mu;  // for the residual updates
         }
     }
 #pragma unroll
@@ -221,7 +221,7 @@ hipError_t launch_gemm_tiled(GemmEpi epi, const GemmArgs& a, hipStream_t s) {
     // Two co-resident workgroups matter more than tile size or prefetch depth: with 64x64 wavefront
     // tiles LDS reads alone need as many cycles as the MFMAs, so a second workgroup fills the gaps.
     if (a.ln_c1) {  // LayerNorm folded around the product
-        if (!a.ln_c2 || !a.stats_in || !a.mu_hat_in || !a.mu_hat_out || a.stat_tiles < 2 || a.stat_tiles % 2 != 0 || a.stat_tiles > 64)
+        if (!a.ln_c2 || !a.stats_in || !a.mu_hat_in || a.stat_tiles < 2 || a.stat_tiles % 2 != 0 || a.stat_tiles > 64)
             return hipErrorInvalidValue;
         switch (epi) {
             case EPI_QKV: return launch_tiled_one<EPI_QKV, 4, 4, 1, true>(a, s);

@@ -25,6 +25,10 @@ enum GemmEpi { EPI_QKV = 0, EPI_RESID = 1, EPI_F32 = 2, EPI_RELU_T = 3, EPI_CROS
 
 struct GemmArgs {
     const void* A;        // PRO_LN: float [M,K] (residual stream); PRO_T: T [M,K]; both in fragment order
+    int n_raw;            // PRO_LNS + EPI_QKV, streaming kernel: columns [n_raw, N) (n_raw = 3 d_model) are not normalised and not
+    float* out2;          // part of q/k/v: their bare sums plus raw_bias go to out2, float [M, N - n_raw] row-major.  0: no such columns
+    const float* raw_bias;  // [N - n_raw]
+    const float* addend;  // PRO_T / PRO_LN + EPI_F32, streaming kernel, may be null: float [M,N] row-major added to the result
     const void* W;        // T [N,K] in fragment order (launch_reorder_weight)
     const void* bias;     // T [N] or null
     const void* ln_g;     // T [K]  (PRO_LN)
@@ -55,7 +59,7 @@ struct GemmArgs {
                              // EPI_RESID_S: [M] row means before the update = the shift to write the shadow with
     const float* ln_c1;      // PRO_LNS: [N]
     const float* ln_c2;      // PRO_LNS: [N] (takes the place of bias)
-    float* mu_hat_out;       // PRO_LNS: [M] row means of A's rows, for the residual update that follows
+    float* mu_hat_out;       // PRO_LNS, may be null: [M] row means of A's rows, for the residual updates that follow
     float2* stats_out;       // EPI_RESID_S: of the updated rows
     void* shadow_out;        // EPI_RESID_S: T [M,N] fragment order
     int stat_tiles, m_stride;
@@ -83,8 +87,29 @@ hipError_t launch_reorder_rows(Dtype dt, const void* src, const int* row_map, vo
 hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b, const void* bias, float* c1, float* c2,
                           int N, int K, hipStream_t s);
 // dst (fragment order) <- src (row-major [N,K]), each column k multiplied by gain[k] if gain is given (T [K];
-// the product is rounded to T once); N % 16 == 0, K % 64 == 0
-hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s);
+// the product is rounded to T once); N % 16 == 0, K % 64 == 0.  With dst_K > 0 the destination is a fragment-order
+// matrix of dst_K columns and src lands in its columns dst_k0 .. dst_k0 + K.
+hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s,
+                                 int dst_k0 = 0, int dst_K = 0);
+
+// Merged products (bfloat16 mode, at most 128 rows).  A residual update x' = x + Wa . o + ba followed by a LayerNorm
+// product Wb . LN(x') reads, in folded form, Wbg . (x' - mu_hat) = Wbg . (x - mu_hat) + (Wbg . Wa) . o + Wbg . ba.
+// With the matrix product Wbg . Wa formed once at create, the second product no longer waits for the update:
+//   P1 = Wbg . (x - mu_hat) + cb   needs only the shadow of x: computed by the launch that already reads that shadow
+//                             (the QKV product, as extra columns: GemmArgs::n_raw, raw_bias),
+//   P2 = (Wbg . Wa) . o       needs only o: computed in the same launch as the update (launch_gemm_pair), which
+//                             adds P1 to it (GemmArgs::addend),
+// and whoever reads P = P1 + P2 finishes it with the statistics of x' that the update's tiles wrote:
+//   Wb . LN(x') + bb = rstd' * (P - (mu' - mu_hat) * c1) + c2,  cb = Wbg . ba, c1 = Wbg . 1, c2 = Wb . beta + bb.
+// One launch per layer less (self-attention output projection + cross-attention query product).
+// launch_gemm_pair: a0 = the update (EPI_RESID_S), a1 = the product P2 (PRO_T, epilogue epi1 = EPI_F32).
+hipError_t launch_gemm_pair(Dtype dt, const GemmArgs& a0, GemmEpi epi1, const GemmArgs& a1, hipStream_t s);
+// P[n,k] = sum_j T(W1[n,j] g[j]) W2[j,k] -> T, fragment order, columns dst_k0.. of a matrix with dst_K columns
+// (W1 [N,J], W2 [J,K] row-major, g null or T [J]; N, K % 64 == 0, J % 16 == 0); bfloat16 only
+hipError_t launch_weight_product(Dtype dt, const void* W1, const void* g, const void* W2, void* dst, int N, int J, int K,
+                                 int dst_k0, int dst_K, hipStream_t s);
+// out[n] = sum_j T(W[n,j] g[j]) v[j] (v null: zeros); bfloat16 only
+hipError_t launch_fold_vec(Dtype dt, const void* W, const void* g, const void* v, float* out, int N, int J, hipStream_t s);
 
 // ---------------------------------------------------------------- decode attention
 struct AttnArgs {
@@ -113,6 +138,14 @@ struct AttnArgs {
     int max_chunks;
     int n_heads, head_dim;
     float scale_log2e;    // log2(e) / sqrt(Dh)
+    // cross-attention behind merged products (see "merged products" above): q holds P, and the kernel finishes it
+    // with the statistics of the updated rows: q = rstd' (P - (mu' - mu_hat) c1) + c2.  q_stats null: q is final.
+    const float2* q_stats;  // [q_stat_tiles][q_m_stride] tile statistics of the updated rows
+    const float* q_mu_hat;  // [B] shift of the shadow that P was computed from
+    const float* q_c1;      // [d_model]
+    const float* q_c2;
+    float q_eps;
+    int q_stat_tiles, q_m_stride, q_rms;
 };
 hipError_t launch_attn_self(Dtype dt, const AttnArgs& a, hipStream_t s);
 hipError_t launch_attn_cross(Dtype dt, const AttnArgs& a, hipStream_t s);
