@@ -341,7 +341,7 @@ void ln_consumer(const aed_decoder* d, GemmArgs& g, const float* c1, const float
 
 // Small batches in bfloat16 mode: the cross-attention query product is split over the QKV launch and the launch of the
 // self-attention output projection (kernels.h, "merged products"): one launch fewer per layer.
-constexpr int kMergeMaxRows = 128;
+constexpr int kMergeMaxRows = 256;
 bool merged_products(const aed_decoder* d) { return folded_ln(d) && d->batch <= kMergeMaxRows; }
 
 hipError_t k_ln_qkv(aed_decoder* d, int l) {

@@ -164,13 +164,15 @@ __global__ __launch_bounds__(64 * NW, sizeof(KV) <= 2 ? 4 : 1) void attn_decode_
         load_f32<EPL>(a.q + qo, q);
         if constexpr (!SELF) {
             q_fix = a.q_stats != nullptr;
-            if (q_fix) {
+            // Only the first wavefront fetches what finishes the query (the row's tile statistics -- at most 64, one
+            // lane each, 64 separate lines -- and the two vectors); it hands the others rstd' and the vector
+            // c2 - rstd' (mu' - mu_hat) c1 through LDS.  Eight wavefronts fetching the same things cost 0.8 us of
+            // load issue in front of the first key blocks.
+            if (q_fix && wave == 0) {
                 const int n0 = h * DH + r * EPL;
                 load_f32<EPL>(a.q_c1 + n0, qc1);
                 load_f32<EPL>(a.q_c2 + n0, qc2);
-                // the row's tile statistics (at most 64: one lane each) are 64 separate lines: only the first wavefront
-                // gathers them and hands the two numbers that come out to the others through LDS
-                if (wave == 0 && lane < a.q_stat_tiles) q_st = a.q_stats[(size_t)lane * a.q_m_stride + b];
+                if (lane < a.q_stat_tiles) q_st = a.q_stats[(size_t)lane * a.q_m_stride + b];
                 q_muh = a.q_mu_hat[b];
             }
         }
@@ -198,20 +200,25 @@ __global__ __launch_bounds__(64 * NW, sizeof(KV) <= 2 ? 4 : 1) void attn_decode_
     if constexpr (!SELF) {
         if (fin) return;
         if (q_fix) {  // q = rstd' (P - (mu' - mu_hat) c1) + c2 with this row's statistics
-            __shared__ float sm_fix[2];
+            __shared__ float sm_fix[DH + 1];
             if (wave == 0) {
                 const int tiles = a.q_stat_tiles;
                 float mu = wave_sum(q_st.x) / (float)tiles;
                 const float dev = lane < tiles ? (q_st.x - mu) * (q_st.x - mu) : 0.f;
                 const float m2 = wave_sum(q_st.y) + 16.f * wave_sum(dev);
                 const float r0 = fold_norm(a.q_rms, 16.f * (float)tiles, a.q_eps, m2, mu);
-                if (lane == 0) { sm_fix[0] = r0; sm_fix[1] = mu - q_muh; }
+                const float sh = r0 * (mu - q_muh);
+                if (g == 0) {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) sm_fix[r * EPL + e] = qc2[e] - sh * qc1[e];
+                }
+                if (lane == 0) sm_fix[DH] = r0;
             }
             // LDS only: the key / value loads in flight are not waited for here
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-            const float rstd = sm_fix[0], shift = sm_fix[1];
+            const float rstd = sm_fix[DH];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) q[e] = rstd * (q[e] - shift * qc1[e]) + qc2[e];
+            for (int e = 0; e < EPL; ++e) q[e] = rstd * q[e] + sm_fix[r * EPL + e];
         }
     }
 #pragma unroll

@@ -560,7 +560,7 @@ static hipError_t launch_pair_one(const GemmArgs& a0, const GemmArgs& a1, hipStr
 }
 template <typename T, int EPI1>
 static hipError_t launch_pair_epi(const GemmArgs& a0, const GemmArgs& a1, hipStream_t s) {
-    // 16 x 16 or 32 x 32 tiles for each of the two (the batches this is used for have at most 128 rows)
+    // 16 x 16 or 32 x 32 tiles for each of the two (the batches this is used for have at most 256 rows)
     const int t0 = choose_tile<T, PRO_T>(a0) > 0, t1 = choose_tile<T, PRO_T>(a1) > 0;
     if (a0.N % 32 != 0 || a1.N % 32 != 0) return hipErrorInvalidValue;
     if (!t0 && !t1) return launch_pair_one<T, 1, 1, EPI1, 1, 1>(a0, a1, s);
@@ -570,7 +570,7 @@ static hipError_t launch_pair_epi(const GemmArgs& a0, const GemmArgs& a1, hipStr
 }
 
 hipError_t launch_gemm_pair(Dtype dt, const GemmArgs& a0, GemmEpi epi1, const GemmArgs& a1, hipStream_t s) {
-    if (dt != kBF16 || a0.M < 1 || a0.M != a1.M || a0.M > 128 || a0.K % 256 != 0 || a1.K % 256 != 0) return hipErrorInvalidValue;
+    if (dt != kBF16 || a0.M < 1 || a0.M != a1.M || a0.M > 256 || a0.K % 256 != 0 || a1.K % 256 != 0) return hipErrorInvalidValue;
     if (!a0.stats_out || !a0.mu_hat_in || !a0.shadow_out || a0.stat_tiles < 4 || a0.stat_tiles % 4 != 0 ||
         a0.stat_tiles * 16 != a0.N || a0.stat_tiles > 4 * kMaxStatTilesPerGroup)
         return hipErrorInvalidValue;
