@@ -61,8 +61,40 @@ __device__ __forceinline__ void gemm_decode_body(const GemmArgs& a, const int bx
         return reinterpret_cast<const T*>(W + frag_block_off<ES>((n0 >> 4) + nt, i * 4 + wave, K));
     };
 
-    // Epilogue operands do not depend on the product: fetch them first so their latency
-    // overlaps the operand stream.
+    // ---- the operand stream (everything but the float32-mode LayerNorm prologue)
+    const char* __restrict__ A = static_cast<const char*>(a.A);
+    // U blocks are fetched per group, two groups in flight (register double buffer)
+    constexpr int U = (MT + NT) <= 2 ? 4 : ((MT + NT) <= 4 ? 2 : 1);
+    Frag16<T> af[2][U][MT], wf[2][U][NT];
+    auto fetch = [&](int buf, int blk0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = blk0 + u;
+            if (i < nblk) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) wf[buf][u][nt] = WNT ? load_frag_nt(wblk(nt, i), lane) : load_frag(wblk(nt, i), lane);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    af[buf][u][mt] = load_frag(
+                        reinterpret_cast<const T*>(A + frag_block_off<ES>((m0 >> 4) + mt, i * 4 + wave, K)), lane);
+            }
+        }
+    };
+    auto compute = [&](int buf, int blk0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (blk0 + u < nblk)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) mma(acc[mt][nt], wf[buf][u][nt], af[buf][u][mt]);
+    };
+    // The stream's first requests go out before anything else: every request in front of them (the epilogue's
+    // operands below are a dozen or two per wavefront) holds the whole stream back by its issue time.
+    if constexpr (PRO != PRO_LN) fetch(0, 0);
+
+    // Epilogue operands do not depend on the product: they are requested here, behind the stream's first group, and
+    // have long arrived when the stream is through.
     constexpr bool LNS = PRO == PRO_LNS;         // LayerNorm folded around the product (see kernels.h)
     constexpr bool RS = EPI == EPI_RESID_S;      // residual update that also writes shadow and statistics
     constexpr bool RES = EPI == EPI_RESID || RS;
@@ -249,34 +281,6 @@ __device__ __forceinline__ void gemm_decode_body(const GemmArgs& a, const int bx
             }
         }
     } else {
-        const char* __restrict__ A = static_cast<const char*>(a.A);
-        // U blocks are fetched per group, two groups in flight (register double buffer)
-        constexpr int U = (MT + NT) <= 2 ? 4 : ((MT + NT) <= 4 ? 2 : 1);
-        Frag16<T> af[2][U][MT], wf[2][U][NT];
-        auto fetch = [&](int buf, int blk0) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = blk0 + u;
-                if (i < nblk) {
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) wf[buf][u][nt] = WNT ? load_frag_nt(wblk(nt, i), lane) : load_frag(wblk(nt, i), lane);
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        af[buf][u][mt] = load_frag(
-                            reinterpret_cast<const T*>(A + frag_block_off<ES>((m0 >> 4) + mt, i * 4 + wave, K)), lane);
-                }
-            }
-        };
-        auto compute = [&](int buf, int blk0) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (blk0 + u < nblk)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) mma(acc[mt][nt], wf[buf][u][nt], af[buf][u][mt]);
-        };
-        fetch(0, 0);
         for (int b0 = 0; b0 < nblk; b0 += 2 * U) {
             fetch(1, b0 + U);
             compute(0, b0);
