@@ -92,7 +92,7 @@ hipError_t launch_fold_ln(Dtype dt, const void* W, const void* g, const void* b,
 hipError_t launch_reorder_weight(Dtype dt, const void* src, const void* gain, void* dst, int N, int K, hipStream_t s,
                                  int dst_k0 = 0, int dst_K = 0);
 
-// Merged products (bfloat16 mode, at most 128 rows).  A residual update x' = x + Wa . o + ba followed by a LayerNorm
+// Merged products (bfloat16 mode, at most 256 rows).  A residual update x' = x + Wa . o + ba followed by a LayerNorm
 // product Wb . LN(x') reads, in folded form, Wbg . (x' - mu_hat) = Wbg . (x - mu_hat) + (Wbg . Wa) . o + Wbg . ba.
 // With the matrix product Wbg . Wa formed once at create, the second product no longer waits for the update:
 //   P1 = Wbg . (x - mu_hat) + cb   needs only the shadow of x: computed by the launch that already reads that shadow
@@ -165,7 +165,7 @@ struct ShadowArgs {
     float2* stats;      // [d / 16][m_stride]: mean and sum of squared deviations of every 16-column tile
     float* mu_hat;      // [B] row means (the shadow's shift)
     int m_stride;
-    int rms;            // RMSNorm: the shadow is x * g and the shift 0
+    int rms;            // RMSNorm: the shift is 0 (the shadow is x itself in the storage type)
 };
 // x[b,:] = emb_scale * tok_emb[cur_tok[b]] + pos_emb[seq_len[b]]   (x in fragment order); d_model <= 1024
 hipError_t launch_embed(Dtype dt, float* x, const void* tok_emb, const void* pos_emb, const StateArgs& st,

@@ -148,6 +148,33 @@ def test_split_chunks_and_capacity_slack(torch_cuda, oracle):
     dec.close()
 
 
+@pytest.mark.parametrize("dtype,n_short", [("fp32", 2), ("bf16", 2), ("bf16", 31)])
+def test_longest_and_shortest_sequence_in_one_batch(torch_cuda, oracle, dtype, n_short):
+    """The most frames the library takes for one sequence (65 535: key offsets and counts are 16-bit fields of a
+    cross-attention work item) next to sequences of a single frame.  With 3 sequences the long one is cut into the
+    largest number of chunks and merged; with 32 (x 4 heads: enough work items not to cut) it is one work item of
+    65 535 keys.  One frame more is refused before anything is launched."""
+    from tests import gpu_util as G
+    from paper_2503_05931_amd import binding
+    lens = [1, 65535] + [1] * (n_short - 1)
+    wl = unit_workload(dtype, 256, 4, 64, lens, seed=88, max_new=8)
+    S = 6
+    toks = random_tokens(wl.cfg, len(lens), S, 12)
+    ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL[dtype])
+    print(f"65 535 frames, {dtype}: max |dlogit| = {err:.2e}")
+    k_ref, v_ref = oracle.Model(wl.cfg, wl.weights).cross_kv(1, wl.subset([1]).enc)
+    k_gpu, v_gpu = dec.aed_read_cross_kv(1, 1, 65535)
+    tol_kv = 1e-5 if dtype == "fp32" else 2e-2
+    assert np.abs(k_gpu - k_ref).max() <= tol_kv and np.abs(v_gpu - v_ref).max() <= tol_kv
+    with pytest.raises(binding.AedError) as ei:
+        dec.aed_cross_kv_precompute(dec.to_device(wl.enc), [1, 65536] + [1] * (n_short - 1))
+    assert ei.value.status == binding.AED_EUNSUPPORTED
+    dec.close()
+
+
 def test_padded_entry_point_equals_packed(torch_cuda, oracle):
     from tests import gpu_util as G
     torch = torch_cuda
