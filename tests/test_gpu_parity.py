@@ -175,6 +175,27 @@ def test_longest_and_shortest_sequence_in_one_batch(torch_cuda, oracle, dtype, n
     dec.close()
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_long_decode_many_self_chunks(torch_cuda, oracle, dtype):
+    """A decode of 1 100 positions for a batch of two: the paged self-attention cache grows to 69 pages per sequence and
+    is read in the largest number of chunks (the small batch has its long sequences cut), merged by the last arriver."""
+    from tests import gpu_util as G
+    S = 1100
+    wl = unit_workload(dtype, 256, 4, 64, [40, 9], seed=91, max_new=S - 4)
+    toks = random_tokens(wl.cfg, 2, S, 13)
+    m = oracle.Model(wl.cfg, wl.weights)
+    ref = m.decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL[dtype])
+    print(f"{S} positions, {dtype}: max |dlogit| = {err:.2e}, near ties {near}")
+    Kr, Vr = m.self_kv(1, wl.subset([1]).enc, toks[1])
+    Ks, Vs = dec.aed_read_self_kv(1, 1)
+    assert Ks.shape == (S, 256)
+    assert np.abs(Ks - Kr).max() <= G.TOL[dtype] and np.abs(Vs - Vr).max() <= G.TOL[dtype]
+    dec.close()
+
+
 def test_padded_entry_point_equals_packed(torch_cuda, oracle):
     from tests import gpu_util as G
     torch = torch_cuda
