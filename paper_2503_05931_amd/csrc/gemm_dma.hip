@@ -289,7 +289,8 @@ hipError_t launch_gemm_dma_crosskv(const GemmArgs& a, hipStream_t s) {
     });
     if (e != hipSuccess) return e;
     const int tiles = ((a.M + kBM - 1) / kBM) * (a.N / kBN);
-    const int grid = tiles >= 256 ? 256 : (tiles + 7) / 8 * 8;  // one workgroup per CU, whole rounds over the XCDs
+    const int grid = persistent_grid(tiles);  // at most one workgroup per CU, whole rounds over the XCDs
+    if (grid <= 0) return hipErrorInvalidDevice;
     if (a.kv_fp8) hipLaunchKernelGGL(gemm_dma_crosskv_kernel<true>, dim3(grid), dim3(512), kLds, s, a);
     else hipLaunchKernelGGL(gemm_dma_crosskv_kernel<false>, dim3(grid), dim3(512), kLds, s, a);
     return hipGetLastError();

@@ -255,7 +255,8 @@ static hipError_t launch_dma128_one(const GemmArgs& a, hipStream_t s) {
     });
     if (e != hipSuccess) return e;
     const int tiles = ((a.M + kBM - 1) / kBM) * (a.N / kBN);
-    const int grid = tiles >= 256 ? 256 : (tiles + 7) / 8 * 8;  // at most one workgroup per CU, whole rounds over the XCDs
+    const int grid = persistent_grid(tiles);  // at most one workgroup per CU, whole rounds over the XCDs
+    if (grid <= 0) return hipErrorInvalidDevice;
     hipLaunchKernelGGL((gemm_dma128_kernel<EPI, LNS>), dim3(grid), dim3(256), kLds, s, a);
     return hipGetLastError();
 }
