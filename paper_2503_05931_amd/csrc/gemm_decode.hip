@@ -465,10 +465,11 @@ static int choose_tile(const GemmArgs& a) {
         const long wgs = (long)((a.M + bm - 1) / bm) * (a.N / bn);
         // Workgroups of the smaller tiles share a CU (two or three fit by registers), so beyond 256 workgroups the
         // bytes through a CU grow in proportion, not in whole rounds.  The 64 x 64 tile runs one workgroup per CU
-        // and its long serial stream costs about half more than its bytes say (measured at M = 256:
-        // 9.7 us against 8.2 us for the 32 x 64 tile on the QKV product).
+        // and its stream costs about half more than its bytes say when K is short (measured at M = 256, K = 1024:
+        // 9.7 us against 8.2 us for the 32 x 64 tile on the QKV product); over K = 4096 the start-up is a smaller
+        // part and the bytes decide (second FFN product at M = 1024: 18.1 us against 19.4 us for 32 x 64).
         const double rounds = wgs > 256 ? (double)wgs / 256.0 : 1.0;
-        const double cost = rounds * (bm * a_bytes + bn * w_bytes) * (c == 4 ? 1.6 : 1.0);
+        const double cost = rounds * (bm * a_bytes + bn * w_bytes) * (c == 4 && a.K < 4096 ? 1.6 : 1.0);
         if (cost < best_cost || (cost == best_cost && wgs < best_wgs)) { best = c; best_cost = cost; best_wgs = wgs; }
     }
     return best;

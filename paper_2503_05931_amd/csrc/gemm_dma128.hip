@@ -59,6 +59,17 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
     const int t_begin = xcd * per_xcd, t_end = min(total, t_begin + per_xcd);
     const int my_tiles = t_begin + j_in < t_end ? (t_end - (t_begin + j_in) + per_x - 1) / per_x : 0;
     if (my_tiles == 0) return;
+    // Tile numbering.  An XCD works on a contiguous run of per_xcd tiles and fetches, through its L2, every row panel
+    // of A and every column panel of W that the run touches (panels of equal size).  Numbered column-fastest, a run
+    // covers few row panels and many column panels; row-fastest, the other way round.  Whichever touches fewer panels
+    // is used: for a decode step's projections (8 row panels, 24 or 32 column panels) that is row-fastest, 11 or 12
+    // panels per XCD instead of 25 or 33, and the run's panels then fit the 4 MB of L2.
+    const int run = min(per_xcd, total);
+    const bool m_fast = min(run, n_mt) + (run + n_mt - 1) / n_mt < (run + n_nt - 1) / n_nt + min(run, n_nt);
+    auto tile_pos = [&](int tile, int& tm, int& tn) {
+        if (m_fast) { tn = tile / n_mt; tm = tile - tn * n_mt; }
+        else { tm = tile / n_nt; tn = tile - tm * n_nt; }
+    };
     const char* __restrict__ A = static_cast<const char*>(a.A);
     const char* __restrict__ W = static_cast<const char*>(a.W);
 
@@ -67,7 +78,8 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
     const size_t row_bytes = (size_t)nk * 2048;  // one row of 16-row blocks
     auto set_tile_ptrs = [&](int ti) {
         const int tile = t_begin + j_in + ti * per_x;
-        const int tm = tile / n_nt, tn = tile - tm * n_nt;
+        int tm, tn;
+        tile_pos(tile, tm, tn);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int q = wave * 4 + jj;
@@ -114,7 +126,8 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
     float stat_n = 0.f;
     auto load_row_stats = [&](int ti) {
         const int tile = t_begin + j_in + ti * per_x;
-        const int tm = tile / n_nt;
+        int tm, tn_unused;
+        tile_pos(tile, tm, tn_unused);
         const int row = tid & 127, grp = tid >> 7, per = a.stat_tiles >> 1;
         stat_n = 16.f * (float)per;
         const float2* sp = a.stats_in + (size_t)(grp * per) * a.m_stride + (tm * kBM + row);
@@ -136,7 +149,28 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
         row_stat[1][grp][row] = m2 + 16.f * dev;
     };
 
+    // EPI_QKV: where the cache slot of each of this lane's two rows starts (element index for head 0; -1: the row is
+    // finished or beyond M).  Position and page are two dependent loads per row: fetched here, at the start of a
+    // tile, they are long there when the epilogue stores the keys and values.
+    long long kv_base[2] = {-1, -1};
+    auto load_kv_rows = [&](int ti) {
+        const int tile = t_begin + j_in + ti * per_x;
+        int tm, tn_unused;
+        tile_pos(tile, tm, tn_unused);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const int m = tm * kBM + wm * 64 + mt * 32 + r32;
+            kv_base[mt] = -1;
+            if (m < a.M && !a.finished[m]) {
+                const int pos = a.seq_len[m];
+                const int page = a.page_table[(size_t)m * a.max_pages + (pos >> 4)];
+                kv_base[mt] = ((long long)page * a.n_heads * kPage + (pos & 15)) * a.head_dim;
+            }
+        }
+    };
+
     set_tile_ptrs(0);
+    if constexpr (EPI == EPI_QKV) load_kv_rows(0);
     for (int s = 0; s < S - 1; ++s) {  // nk >= 8: all inside the first tile
 #pragma unroll
         for (int j = 0; j < 8; ++j) request_one(j);
@@ -145,7 +179,6 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
     if constexpr (LNS) load_row_stats(0);
     wait_loads_barrier<0>();  // steps 0 .. S-2 have landed
     Frags f0, f1;
-    read_frags(0, 0, f0);
     int slot = 0;  // slot of the step being computed
 
     auto mfma4 = [&](const Frags& f) {
@@ -159,9 +192,10 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
     auto step = [&](auto waited_before) {
         __builtin_amdgcn_sched_barrier(0);
         if (decltype(waited_before)::value) wait_lds_barrier();
-        else wait_loads_barrier<(S - 3) * 8>();  // the requests of the step after the next may be in flight
+        else wait_loads_barrier<(S - 2) * 8>();  // the requests of the two steps after this one may be in flight
         const int cur = slot;
         slot = slot == S - 1 ? 0 : slot + 1;
+        read_frags(cur, 0, f0);
         read_frags(cur, 1, f1);
         mfma4(f0);
         request_one(0); request_one(1);
@@ -174,7 +208,6 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
         mfma4(f0);
         request_one(4); request_one(5);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(slot, 0, f0);  // first fragments of the next step
         mfma4(f1);
         request_one(6); request_one(7);
         request_done();
@@ -189,6 +222,7 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
             wait_lds_barrier();  // every wavefront is through the previous tile's epilogue
             load_row_stats(ti);
         }
+        if (EPI == EPI_QKV && ti > 0) load_kv_rows(ti);
 #pragma unroll 1
         for (int ks = 0; ks < S - 2; ++ks) step(std::true_type{});  // waited for at the end of the previous tile
 #pragma unroll 1
@@ -200,7 +234,8 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
         // ---- the tile is complete: everything requested so far has landed, so that the stores below may stay
         // in flight over the next tile's first S-2 steps
         const int tile = t_begin + j_in + ti * per_x;
-        const int tm = tile / n_nt, tn = tile - tm * n_nt;
+        int tm, tn;
+        tile_pos(tile, tm, tn);
         wait_loads_barrier<0>();
         const int m_base = tm * kBM + wm * 64, n_base = tn * kBN + wn * 64;
         float rstd[2], shift[2];
@@ -237,7 +272,20 @@ __global__ __launch_bounds__(256) void gemm_dma128_kernel(GemmArgs a) {
                     if (m >= a.M) continue;
                     if constexpr (LNS) v = (v - shift[mt] * c1) * rstd[mt] + bv;
                     else v += bv;
-                    gemm_epilogue<T, EPI>(a, m, n, v, f32x4{0.f, 0.f, 0.f, 0.f});
+                    if constexpr (EPI == EPI_QKV) {
+                        const int d = a.d_model;
+                        if (n < d) {
+                            store4(static_cast<float*>(a.out) + (size_t)m * d + n, v);
+                        } else if (kv_base[mt] >= 0) {
+                            const int which = n >= 2 * d;
+                            const int c = n - (which ? 2 * d : d);
+                            const long long at = kv_base[mt] + (long long)(c / a.head_dim) * kPage * a.head_dim + c % a.head_dim;
+                            if (a.kv_fp8) store4_fp8(static_cast<unsigned char*>(which ? a.v_pool : a.k_pool) + at, v);
+                            else store4(static_cast<T*>(which ? a.v_pool : a.k_pool) + at, v);
+                        }
+                    } else {
+                        gemm_epilogue<T, EPI>(a, m, n, v, f32x4{0.f, 0.f, 0.f, 0.f});
+                    }
                 }
             }
         zero_acc();
