@@ -133,6 +133,23 @@ def test_very_large_batches_tiled_projections(torch_cuda, oracle, d_model, n_hea
     dec.close()
 
 
+def test_wide_ffn_large_batch_row_fastest_tiles(torch_cuda, oracle):
+    """700 rows against a 4 096-wide first FFN product: 6 x 32 tiles of 128 x 128 on the direct-to-LDS kernel, which
+    then numbers its tiles row-fastest (an XCD's run of 24 tiles = all 6 row panels x 4 column panels), with a
+    ragged last row tile (60 rows)."""
+    from tests import gpu_util as G
+    batch = 700
+    enc_lens = [1 + (3 * i) % 5 for i in range(batch)]
+    wl = unit_workload("bf16", 512, 4, 128, enc_lens, seed=batch, max_new=8, d_ffn=4096)
+    toks = random_tokens(wl.cfg, batch, 3, 8)
+    ref = oracle.Model(wl.cfg, wl.weights).decode_forced(wl.enc, wl.enc_lens, toks)
+    dec = G.make_decoder(wl)
+    glog, gids = G.forced_logits_gpu(dec, wl, toks)
+    err, near = G.check_forced(ref, glog, gids, G.TOL["bf16"])
+    print(f"batch {batch}, d_ffn 4096: max |dlogit| = {err:.2e}, near ties {near}")
+    dec.close()
+
+
 def test_split_chunks_and_capacity_slack(torch_cuda, oracle):
     """Few long sequences: the work lists cut keys into several chunks per (sequence, head) and
     the last-arriver merge runs; capacities larger than the batch leave unused slots poisoned."""
