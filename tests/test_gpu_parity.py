@@ -332,6 +332,7 @@ def test_tiled_mfma_cross_kv_precompute(torch_cuda, oracle):
 
 @pytest.mark.parametrize("d_model,n_heads,head_dim,enc_lens", [
     (1024, 8, 128, [700] * 7 + [411]),      # 5 311 frames: 21 row tiles (the last one ragged) x 8 column tiles of 256
+    (1024, 16, 64, [900] * 5 + [677]),      # K = 1024 with heads of 64: two heads per 128-column wavefront tile
     (512, 8, 64, [1300] * 7 + [1150]),      # 10 250 frames: 41 x 4 tiles, one head per 64 columns
     (768, 12, 64, [1000] * 7 + [77]),       # 7 077 frames, K = 768 (24 k-steps of 32): 28 x 6 tiles
     (768, 12, 64, [500] * 7),               # 3 500 frames: too few 256-tiles, 28 x 12 tiles of 128 x 128 instead
